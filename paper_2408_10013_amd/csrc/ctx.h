@@ -1,0 +1,131 @@
+// Internal declarations shared by the host-side sources of libssdt: the context (tensor
+// cache registry, device arena, copy backend).  Not part of the public interface.
+#pragma once
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <cstring>
+#include <deque>
+#include <map>
+#include <memory>
+#include <string>
+#include <unordered_map>
+#include <vector>
+
+#include "ssdt.h"
+
+namespace ssdt {
+
+constexpr size_t kAlignTensor = 256;
+constexpr size_t kAlignPack = 4096;
+inline size_t up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// An event of the copy backend.  For the HIP backend `h` is a hipEvent_t; for the
+// simulated backend `done` is flipped by ssdt_sim_complete.
+struct Ev {
+  void *h = nullptr;
+  bool done = true;
+  bool timing = false;
+  int refs = 0;  // holders: free blocks, records, pending wait measurements
+};
+
+// What the registry needs from the machine: events, cross-stream waits and the two
+// in-order copy queues (store = device to host, load = host to device).
+class Backend {
+ public:
+  virtual ~Backend() {}
+  virtual bool is_sim() const = 0;
+  virtual Ev *record(ssdt_stream s, bool timing) = 0;             // event after s's current work
+  virtual void wait(ssdt_stream s, Ev *e) = 0;                    // s waits for e
+  virtual bool done(Ev *e) = 0;
+  virtual Ev *copy(int dir, void *dst, const void *src, size_t n, Ev *after) = 0;
+  virtual void wait_queue(int dir, Ev *e) = 0;                    // a copy queue waits for e
+  virtual ssdt_stream queue_stream(int dir) = 0;                  // identity of a copy queue as a stream
+  virtual void recycle(Ev *e) = 0;
+  virtual double elapsed_ms(Ev *a, Ev *b) = 0;
+  virtual void sync_io() = 0;
+  virtual void host_sync_event(Ev *e) = 0;
+  virtual int sim_complete(int dir, int n) { (void)dir; (void)n; return -1; }
+  virtual void *pool() = 0;
+  std::string err;  // last backend failure ("" = none)
+};
+Backend *make_hip_backend(size_t pool_bytes, std::string *err);
+Backend *make_sim_backend(size_t pool_bytes, std::string *err);
+
+struct Block {
+  size_t size = 0;
+  bool free = true;
+  int refs = 0;
+  Ev *ready = nullptr;            // free block: later users on another stream wait for this
+  ssdt_stream ready_stream = nullptr;
+};
+
+struct Rec {
+  ssdt_tid tid = 0;
+  int32_t layer = 0, cls = 0, state = 0;
+  uint64_t bytes = 0;
+  int64_t pack_offset = -1, pool_offset = -1;
+  void *dev = nullptr;
+  bool in_arena = false;
+  bool holds_ref = false;     // the registry holds a reference on dev's arena block
+  bool stored = false;        // a host copy exists or is being written
+  bool forwarded = false;
+  bool release_pending = false;  // released while its store was still in flight
+  bool load_waited = false;
+  std::vector<int32_t> scopes;
+  Ev *store_ev = nullptr, *load_ev = nullptr;
+};
+
+struct WaitPair { Ev *a, *b; int kind; };
+
+struct Ctx {
+  ssdt_config cfg{};
+  std::unique_ptr<Backend> be;
+  std::string last_error;
+  // arena
+  std::map<size_t, Block> blocks;  // offset -> block
+  uint64_t in_use = 0, peak_in_use = 0, high_water = 0, n_allocs = 0;
+  // registry
+  int32_t num_layers = 0;
+  std::vector<std::pair<const char *, size_t>> weights;
+  std::vector<int32_t> stack;
+  std::vector<int32_t> bwd_open;
+  uint64_t next_stamp = 1;
+  std::vector<Rec> recs;
+  std::unordered_map<const void *, size_t> by_storage;
+  std::unordered_map<ssdt_tid, size_t> by_tid;
+  std::map<int32_t, size_t> pack_base, pack_cursor;
+  size_t pool_cursor = 0;
+  std::deque<size_t> storing;  // record indices with a store in flight, oldest first
+  ssdt_stats st{};
+  std::vector<WaitPair> waits;
+
+  ssdt_status fail(ssdt_status code, const char *fmt, ...);
+  bool in_arena(const void *p) const {
+    auto c = (const char *)p, b = (const char *)cfg.arena_base;
+    return cfg.arena_base && c >= b && c < b + cfg.arena_bytes;
+  }
+  // arena
+  ssdt_status alloc(size_t bytes, ssdt_stream s, void **out);
+  void ref(void *p);
+  void unref(void *p, Ev *ready, ssdt_stream ready_stream);
+  bool try_alloc(size_t bytes, ssdt_stream s, void **out);
+  // registry
+  void poll();
+  void reclaim(size_t idx);
+  bool is_weight(const void *p) const;
+  ssdt_status save(const void *base, size_t sbytes, size_t view_off, const int64_t *shape, int32_t ndim,
+                   int32_t dtype, ssdt_tid *out);
+  ssdt_status scope_begin(int32_t scope, int32_t phase);
+  ssdt_status scope_end(int32_t scope, int32_t phase);
+  ssdt_status offload(int32_t scope, ssdt_stream producer);
+  ssdt_status prefetch(int32_t scope);
+  ssdt_status get(ssdt_tid tid, ssdt_stream consumer, void **out);
+  ssdt_status release(int32_t scope, ssdt_stream s);
+  ssdt_status step_begin(int32_t n);
+  void timed_wait(ssdt_stream s, Ev *e, int kind);
+};
+
+}  // namespace ssdt
+
+struct ssdt_ctx : ssdt::Ctx {};

@@ -1,0 +1,618 @@
+// The tensor cache: saved-tensor registry, device arena and offload/prefetch engine.
+//
+// Follows the paper's Sec. 3.1 (when offloads and prefetches start, kept last module),
+// Sec. 3.2 (scope stack, pack/unpack hooks, release at scope exit), Sec. 3.3.1 (identity by
+// storage stamp, weight exclusion), Sec. 3.3.2 (two in-order queues, data forwarding) and
+// Algorithm 1 (order of the pack hook's tests).  Everything here is host code; the machine
+// is reached only through `Backend`.
+#include <algorithm>
+
+#include "ctx.h"
+
+namespace ssdt {
+
+ssdt_status Ctx::fail(ssdt_status code, const char *fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  last_error = buf;
+  return code;
+}
+
+static inline Ev *hold(Ev *e) {
+  if (e) ++e->refs;
+  return e;
+}
+static inline void drop(Backend *be, Ev *e) {
+  if (e && --e->refs <= 0) be->recycle(e);
+}
+
+// ---------------------------------------------------------------------------------------
+// arena: first-fit by address over a map of blocks; blocks are reference counted (the
+// caller's reference from alloc, the registry's from save)
+// ---------------------------------------------------------------------------------------
+
+static void tidy(Ctx *c) {
+  // forget ready-events that have completed, then merge neighbouring free blocks that carry none
+  for (auto &kv : c->blocks) {
+    Block &b = kv.second;
+    if (b.free && b.ready && c->be->done(b.ready)) {
+      drop(c->be.get(), b.ready);
+      b.ready = nullptr;
+    }
+  }
+  for (auto it = c->blocks.begin(); it != c->blocks.end();) {
+    auto nx = std::next(it);
+    if (nx != c->blocks.end() && it->second.free && nx->second.free && !it->second.ready && !nx->second.ready) {
+      it->second.size += nx->second.size;
+      c->blocks.erase(nx);
+    } else {
+      it = nx;
+    }
+  }
+}
+
+bool Ctx::try_alloc(size_t bytes, ssdt_stream s, void **out) {
+  for (auto it = blocks.begin(); it != blocks.end(); ++it) {
+    Block &b = it->second;
+    if (!b.free || b.size < bytes) continue;
+    if (b.size > bytes) {
+      Block rest = b;
+      rest.size = b.size - bytes;
+      hold(rest.ready);
+      blocks[it->first + bytes] = rest;
+      b.size = bytes;
+    }
+    if (b.ready) {
+      if (b.ready_stream != s) be->wait(s, b.ready);
+      drop(be.get(), b.ready);
+      b.ready = nullptr;
+    }
+    b.free = false;
+    b.refs = 1;
+    in_use += bytes;
+    peak_in_use = std::max(peak_in_use, in_use);
+    high_water = std::max<uint64_t>(high_water, it->first + bytes);
+    ++n_allocs;
+    *out = (char *)cfg.arena_base + it->first;
+    return true;
+  }
+  return false;
+}
+
+ssdt_status Ctx::alloc(size_t bytes, ssdt_stream s, void **out) {
+  if (!out || bytes == 0) return fail(SSDT_E_INVAL, "arena_alloc: null output or zero size");
+  if (!cfg.arena_base) return fail(SSDT_E_NOMEM, "arena_alloc: the context has no arena");
+  bytes = up(bytes, kAlignTensor);
+  poll();
+  tidy(this);
+  if (try_alloc(bytes, s, out)) return SSDT_OK;
+  // No room: tensors still being stored hold memory that returns once their copy is done
+  // (Sec. 3.2).  Make the requesting stream wait for the oldest stores, in order.
+  while (!storing.empty()) {
+    size_t idx = storing.front();
+    storing.pop_front();
+    Rec &r = recs[idx];
+    if (r.forwarded || r.state != SSDT_ST_STORING) continue;
+    timed_wait(s, r.store_ev, 1);
+    reclaim(idx);
+    tidy(this);
+    if (try_alloc(bytes, s, out)) return SSDT_OK;
+  }
+  return fail(SSDT_E_NOMEM, "arena_alloc: no room for %zu bytes (in use %llu of %zu)", bytes,
+              (unsigned long long)in_use, cfg.arena_bytes);
+}
+
+void Ctx::ref(void *p) {
+  auto it = blocks.find((char *)p - (char *)cfg.arena_base);
+  if (it != blocks.end() && !it->second.free) ++it->second.refs;
+}
+
+void Ctx::unref(void *p, Ev *ready, ssdt_stream ready_stream) {
+  auto it = blocks.find((char *)p - (char *)cfg.arena_base);
+  if (it == blocks.end() || it->second.free) return;
+  Block &b = it->second;
+  if (--b.refs > 0) return;
+  b.free = true;
+  b.ready = hold(ready);
+  b.ready_stream = ready_stream;
+  in_use -= b.size;
+  by_storage.erase(p);  // the address may now be reused by a different storage
+}
+
+// ---------------------------------------------------------------------------------------
+// registry
+// ---------------------------------------------------------------------------------------
+
+bool Ctx::is_weight(const void *p) const {
+  for (auto &w : weights)
+    if ((const char *)p >= w.first && (const char *)p < w.first + w.second) return true;
+  return false;
+}
+
+void Ctx::timed_wait(ssdt_stream s, Ev *e, int kind) {
+  if (cfg.measure_waits && !be->is_sim()) {
+    Ev *a = hold(be->record(s, true));
+    be->wait(s, e);
+    Ev *b = hold(be->record(s, true));
+    waits.push_back({a, b, kind});
+  } else {
+    be->wait(s, e);
+  }
+}
+
+// The store of record idx is complete (or `s` has been ordered after it): its device copy
+// is dropped (Sec. 3.2, "when the tensor finishes offloading, the tensor cache no longer
+// holds a reference to it").
+void Ctx::reclaim(size_t idx) {
+  Rec &r = recs[idx];
+  bool finished = be->done(r.store_ev);
+  if (r.holds_ref) {
+    unref(r.dev, finished ? nullptr : r.store_ev, be->queue_stream(0));
+    r.holds_ref = false;
+  }
+  r.dev = nullptr;
+  r.state = r.release_pending ? SSDT_ST_RELEASED : SSDT_ST_OFFLOADED;
+}
+
+void Ctx::poll() {
+  while (!storing.empty()) {
+    size_t idx = storing.front();
+    Rec &r = recs[idx];
+    if (r.forwarded || r.state != SSDT_ST_STORING) {
+      storing.pop_front();
+      continue;
+    }
+    if (!be->done(r.store_ev)) break;
+    storing.pop_front();
+    reclaim(idx);
+  }
+}
+
+ssdt_status Ctx::step_begin(int32_t n) {
+  if (n <= 0) return fail(SSDT_E_INVAL, "step_begin: num_layers must be positive");
+  if (!stack.empty()) return fail(SSDT_E_STATE, "step_begin: a forward scope is still open");
+  for (auto &r : recs)
+    if (!r.scopes.empty())
+      return fail(SSDT_E_STATE, "step_begin: record %llu of the previous step has not been released",
+                  (unsigned long long)r.tid);
+  poll();
+  if (!storing.empty()) {
+    be->sync_io();
+    poll();
+  }
+  for (auto &r : recs) {
+    drop(be.get(), r.store_ev);
+    drop(be.get(), r.load_ev);
+  }
+  recs.clear();
+  by_storage.clear();
+  by_tid.clear();
+  pack_base.clear();
+  pack_cursor.clear();
+  storing.clear();
+  bwd_open.clear();
+  pool_cursor = 0;
+  num_layers = n;
+  ssdt_stats z{};
+  st = z;
+  peak_in_use = in_use;
+  high_water = 0;
+  for (auto &kv : blocks)
+    if (!kv.second.free) high_water = std::max<uint64_t>(high_water, kv.first + kv.second.size);
+  return SSDT_OK;
+}
+
+ssdt_status Ctx::scope_begin(int32_t scope, int32_t phase) {
+  if (scope < 0) return fail(SSDT_E_INVAL, "scope_begin: negative scope");
+  if (phase == SSDT_FWD) {
+    if (num_layers <= 0) return fail(SSDT_E_STATE, "scope_begin: no step in progress (call ssdt_step_begin)");
+    if (stack.empty() && !pack_base.count(scope)) {
+      pool_cursor = up(pool_cursor, kAlignPack);
+      pack_base[scope] = pool_cursor;
+      pack_cursor[scope] = 0;
+    }
+    stack.push_back(scope);
+    return SSDT_OK;
+  }
+  if (phase == SSDT_BWD) {
+    bwd_open.push_back(scope);
+    return SSDT_OK;
+  }
+  return fail(SSDT_E_INVAL, "scope_begin: unknown phase %d", phase);
+}
+
+ssdt_status Ctx::scope_end(int32_t scope, int32_t phase) {
+  if (phase == SSDT_FWD) {
+    if (stack.empty() || stack.back() != scope)
+      return fail(SSDT_E_STATE, "scope_end: scope %d is not on top of the forward scope stack", scope);
+    stack.pop_back();
+    if (stack.empty()) pool_cursor = up(pack_base[scope] + pack_cursor[scope], kAlignPack);
+    return SSDT_OK;
+  }
+  if (phase == SSDT_BWD) {
+    if (bwd_open.empty() || bwd_open.back() != scope)
+      return fail(SSDT_E_STATE, "scope_end: backward scope %d is not open", scope);
+    bwd_open.pop_back();
+    return SSDT_OK;
+  }
+  return fail(SSDT_E_INVAL, "scope_end: unknown phase %d", phase);
+}
+
+ssdt_status Ctx::save(const void *base, size_t sbytes, size_t view_off, const int64_t *shape, int32_t ndim,
+                      int32_t dtype, ssdt_tid *out) {
+  if (!base || !out || !shape || ndim <= 0 || sbytes == 0) return fail(SSDT_E_INVAL, "save: null or empty argument");
+  if (dtype != SSDT_F32 && dtype != SSDT_BF16) return fail(SSDT_E_INVAL, "save: unknown dtype %d", dtype);
+  if (stack.empty()) return fail(SSDT_E_STATE, "save: no forward scope is open");
+  uint64_t numel = 1;
+  for (int i = 0; i < ndim; ++i) {
+    if (shape[i] < 0) return fail(SSDT_E_INVAL, "save: negative extent");
+    numel *= (uint64_t)shape[i];
+  }
+  size_t esize = dtype == SSDT_F32 ? 4 : 2;
+  if (view_off + numel * esize > sbytes) return fail(SSDT_E_INVAL, "save: the view does not fit its storage");
+  bool arena = in_arena(base);
+  if (arena) {
+    auto it = blocks.find((const char *)base - (const char *)cfg.arena_base);
+    if (it == blocks.end() || it->second.free || it->second.size < sbytes)
+      return fail(SSDT_E_INVAL, "save: storage is inside the arena but is not a live arena block");
+  }
+  ++st.save_calls;
+  if (is_weight(base)) {  // Alg. 1, first test
+    ++st.bypass_weight;
+    *out = 0;
+    return SSDT_OK;
+  }
+  int32_t scope = stack.back(), layer = stack.front();
+  auto hit = by_storage.find(base);
+  if (hit != by_storage.end()) {  // a view of a storage already stamped (Sec. 3.3.1)
+    Rec &r = recs[hit->second];
+    ++st.dedup_hits;
+    if (std::find(r.scopes.begin(), r.scopes.end(), scope) == r.scopes.end()) r.scopes.push_back(scope);
+    *out = r.cls == SSDT_CLS_SMALL ? 0 : r.tid;
+    return SSDT_OK;
+  }
+  Rec r;
+  r.tid = next_stamp++;
+  r.layer = layer;
+  r.bytes = sbytes;
+  r.dev = const_cast<void *>(base);
+  r.in_arena = arena;
+  r.state = SSDT_ST_RESIDENT;
+  r.scopes.push_back(scope);
+  ++st.unique;
+  if (arena) {
+    ref(r.dev);
+    r.holds_ref = true;
+  }
+  if ((int64_t)numel < cfg.min_offload_elems) {  // Alg. 1: too small to be worth a transfer
+    r.cls = SSDT_CLS_SMALL;
+    ++st.bypass_small;
+    st.bytes_small += sbytes;
+    *out = 0;
+  } else {
+    bool in_last = layer >= num_layers - cfg.keep_last;
+    bool over = cfg.budget_bytes >= 0 && st.bytes_offloaded + sbytes > (uint64_t)cfg.budget_bytes;
+    size_t off = up(pack_cursor[layer], kAlignTensor);
+    bool nomem = up(pack_base[layer] + off + sbytes, kAlignPack) > cfg.pool_bytes;
+    if (in_last || over || nomem || !arena) {
+      r.cls = SSDT_CLS_KEPT;
+      ++st.kept;
+      st.bytes_kept += sbytes;
+    } else {
+      r.cls = SSDT_CLS_OFFLOADED;
+      r.pack_offset = (int64_t)off;
+      r.pool_offset = (int64_t)(pack_base[layer] + off);
+      pack_cursor[layer] = off + sbytes;
+      ++st.offloaded;
+      st.bytes_offloaded += sbytes;
+      st.pool_bytes_used = up(pack_base[layer] + pack_cursor[layer], kAlignPack);
+    }
+    *out = r.tid;
+  }
+  by_storage[base] = recs.size();
+  by_tid[r.tid] = recs.size();
+  recs.push_back(r);
+  return SSDT_OK;
+}
+
+ssdt_status Ctx::offload(int32_t scope, ssdt_stream producer) {
+  poll();
+  Ev *after = nullptr;
+  for (size_t i = 0; i < recs.size(); ++i) {
+    Rec &r = recs[i];
+    if (r.layer != scope || r.cls != SSDT_CLS_OFFLOADED || r.state != SSDT_ST_RESIDENT || r.stored || !r.dev)
+      continue;
+    if (!after) {
+      after = hold(be->record(producer, false));
+      be->wait_queue(0, after);  // the copy starts once the producing operators have finished
+    }
+    r.store_ev = hold(be->copy(0, (char *)be->pool() + r.pool_offset, r.dev, r.bytes, nullptr));
+    if (!be->err.empty()) return fail(SSDT_E_HIP, "offload: %s", be->err.c_str());
+    r.stored = true;
+    r.state = SSDT_ST_STORING;
+    storing.push_back(i);
+  }
+  drop(be.get(), after);
+  return SSDT_OK;
+}
+
+ssdt_status Ctx::prefetch(int32_t scope) {
+  poll();
+  std::vector<size_t> todo;
+  for (size_t i = recs.size(); i-- > 0;) {  // reverse of the order recorded in forward (Sec. 3.1)
+    Rec &r = recs[i];
+    if (r.layer != scope || r.cls != SSDT_CLS_OFFLOADED || r.scopes.empty()) continue;
+    if (r.state == SSDT_ST_STORING) {  // still being stored: forward the in-memory copy (Sec. 3.3.2)
+      r.state = SSDT_ST_RESIDENT;
+      r.forwarded = true;
+      ++st.forwarded;
+    } else if (r.state == SSDT_ST_OFFLOADED) {
+      todo.push_back(i);
+    }
+  }
+  ssdt_stream q = be->queue_stream(1);
+  std::vector<void *> slots;
+  for (size_t i : todo) {
+    void *p = nullptr;
+    if (alloc(recs[i].bytes, q, &p) != SSDT_OK) {
+      for (void *s : slots) unref(s, nullptr, nullptr);
+      return SSDT_E_NOMEM;  // message set by alloc; nothing was enqueued
+    }
+    slots.push_back(p);
+  }
+  for (size_t k = 0; k < todo.size(); ++k) {
+    Rec &r = recs[todo[k]];
+    r.dev = slots[k];
+    r.holds_ref = true;  // the reference alloc() gave now belongs to the record
+    by_storage[r.dev] = todo[k];
+    drop(be.get(), r.load_ev);
+    r.load_ev = hold(be->copy(1, r.dev, (char *)be->pool() + r.pool_offset, r.bytes, nullptr));
+    if (!be->err.empty()) return fail(SSDT_E_HIP, "prefetch: %s", be->err.c_str());
+    r.state = SSDT_ST_LOADING;
+    r.load_waited = false;
+    ++st.loads;
+    st.bytes_loaded += r.bytes;
+  }
+  return SSDT_OK;
+}
+
+ssdt_status Ctx::get(ssdt_tid tid, ssdt_stream consumer, void **out) {
+  if (!out) return fail(SSDT_E_INVAL, "get: null output");
+  auto it = by_tid.find(tid);
+  if (tid == 0 || it == by_tid.end()) return fail(SSDT_E_NOTFOUND, "get: unknown tensor id %llu", (unsigned long long)tid);
+  poll();
+  Rec &r = recs[it->second];
+  if (r.state == SSDT_ST_RELEASED || r.scopes.empty())
+    return fail(SSDT_E_STATE, "get: tensor %llu has been released", (unsigned long long)tid);
+  if (r.state == SSDT_ST_STORING) {
+    r.state = SSDT_ST_RESIDENT;
+    r.forwarded = true;
+    ++st.forwarded;
+  } else if (r.state == SSDT_ST_OFFLOADED) {  // nobody prefetched it: load on demand
+    void *p = nullptr;
+    ssdt_stream q = be->queue_stream(1);
+    if (alloc(r.bytes, q, &p) != SSDT_OK) return SSDT_E_NOMEM;
+    r.dev = p;
+    r.holds_ref = true;
+    by_storage[p] = it->second;
+    drop(be.get(), r.load_ev);
+    r.load_ev = hold(be->copy(1, p, (char *)be->pool() + r.pool_offset, r.bytes, nullptr));
+    if (!be->err.empty()) return fail(SSDT_E_HIP, "get: %s", be->err.c_str());
+    r.state = SSDT_ST_LOADING;
+    r.load_waited = false;
+    ++st.loads;
+    ++st.demand_loads;
+    st.bytes_loaded += r.bytes;
+  }
+  if (r.load_ev) {
+    if (!r.load_waited) {
+      timed_wait(consumer, r.load_ev, 0);
+      r.load_waited = true;
+    } else {
+      be->wait(consumer, r.load_ev);
+    }
+    if (r.state == SSDT_ST_LOADING) r.state = SSDT_ST_RESIDENT;
+  }
+  *out = r.dev;
+  return SSDT_OK;
+}
+
+ssdt_status Ctx::release(int32_t scope, ssdt_stream s) {
+  poll();
+  Ev *ev = nullptr;
+  for (auto &r : recs) {
+    auto f = std::find(r.scopes.begin(), r.scopes.end(), scope);
+    if (f == r.scopes.end()) continue;
+    r.scopes.erase(f);
+    if (!r.scopes.empty()) continue;
+    ++st.released;
+    if (r.state == SSDT_ST_STORING && !r.forwarded) {
+      r.release_pending = true;  // its memory returns when the store completes
+      continue;
+    }
+    if (r.holds_ref && r.dev) {
+      if (r.state == SSDT_ST_LOADING) {
+        unref(r.dev, r.load_ev, be->queue_stream(1));
+      } else {
+        if (!ev) ev = hold(be->record(s, false));
+        unref(r.dev, ev, s);
+      }
+      r.holds_ref = false;
+    }
+    r.dev = nullptr;
+    r.state = SSDT_ST_RELEASED;
+  }
+  drop(be.get(), ev);
+  return SSDT_OK;
+}
+
+}  // namespace ssdt
+
+// ---------------------------------------------------------------------------------------
+// C ABI
+// ---------------------------------------------------------------------------------------
+using namespace ssdt;
+
+extern "C" {
+
+const char *ssdt_version(void) { return "ssdt 0.1 (gfx950)"; }
+
+const char *ssdt_last_error(const ssdt_ctx *ctx) { return ctx ? ctx->last_error.c_str() : "null context"; }
+
+ssdt_status ssdt_ctx_create(const ssdt_config *cfg, ssdt_ctx **out) {
+  if (!cfg || !out) return SSDT_E_INVAL;
+  *out = nullptr;
+  if (cfg->arena_bytes && (!cfg->arena_base || ((uintptr_t)cfg->arena_base % kAlignTensor) != 0)) return SSDT_E_INVAL;
+  if (cfg->keep_last < 0 || cfg->min_offload_elems < 0) return SSDT_E_INVAL;
+  if (cfg->spill_path && cfg->spill_path[0]) return SSDT_E_UNSUPPORTED;
+  std::string err;
+  Backend *be = nullptr;
+  if (cfg->backend == SSDT_BACKEND_HIP) be = make_hip_backend(cfg->pool_bytes, &err);
+  else if (cfg->backend == SSDT_BACKEND_SIM) be = make_sim_backend(cfg->pool_bytes, &err);
+  else return SSDT_E_INVAL;
+  if (!be) {
+    fprintf(stderr, "ssdt_ctx_create: %s\n", err.c_str());
+    return cfg->backend == SSDT_BACKEND_HIP ? SSDT_E_HIP : SSDT_E_NOMEM;
+  }
+  auto *c = new ssdt_ctx();
+  c->cfg = *cfg;
+  c->cfg.spill_path = nullptr;
+  c->be.reset(be);
+  if (cfg->arena_bytes) {
+    Block b;
+    b.size = cfg->arena_bytes / kAlignTensor * kAlignTensor;
+    c->blocks[0] = b;
+  }
+  *out = c;
+  return SSDT_OK;
+}
+
+ssdt_status ssdt_ctx_destroy(ssdt_ctx *ctx) {
+  if (!ctx) return SSDT_E_INVAL;
+  ctx->be->sync_io();
+  delete ctx;
+  return SSDT_OK;
+}
+
+ssdt_status ssdt_step_begin(ssdt_ctx *c, int32_t n) { return c ? c->step_begin(n) : SSDT_E_INVAL; }
+
+ssdt_status ssdt_set_budget(ssdt_ctx *c, int64_t b) {
+  if (!c) return SSDT_E_INVAL;
+  c->cfg.budget_bytes = b;
+  return SSDT_OK;
+}
+
+ssdt_status ssdt_arena_alloc(ssdt_ctx *c, size_t bytes, ssdt_stream s, void **out) {
+  return c ? c->alloc(bytes, s, out) : SSDT_E_INVAL;
+}
+
+ssdt_status ssdt_arena_free(ssdt_ctx *c, void *p, ssdt_stream s) {
+  if (!c) return SSDT_E_INVAL;
+  if (!p || !c->in_arena(p)) return c->fail(SSDT_E_INVAL, "arena_free: pointer is not inside the arena");
+  auto it = c->blocks.find((char *)p - (char *)c->cfg.arena_base);
+  if (it == c->blocks.end() || it->second.free) return c->fail(SSDT_E_STATE, "arena_free: not a live arena block");
+  if (it->second.refs > 1) {
+    c->unref(p, nullptr, nullptr);  // the registry still refers to it
+    return SSDT_OK;
+  }
+  Ev *ev = c->be->record(s, false);
+  ++ev->refs;
+  c->unref(p, ev, s);
+  if (--ev->refs <= 0) c->be->recycle(ev);
+  return SSDT_OK;
+}
+
+ssdt_status ssdt_register_weight(ssdt_ctx *c, const void *base, size_t bytes) {
+  if (!c) return SSDT_E_INVAL;
+  if (!base || !bytes) return c->fail(SSDT_E_INVAL, "register_weight: null or empty buffer");
+  c->weights.emplace_back((const char *)base, bytes);
+  return SSDT_OK;
+}
+
+ssdt_status ssdt_scope_begin(ssdt_ctx *c, int32_t scope, int32_t phase) { return c ? c->scope_begin(scope, phase) : SSDT_E_INVAL; }
+ssdt_status ssdt_scope_end(ssdt_ctx *c, int32_t scope, int32_t phase) { return c ? c->scope_end(scope, phase) : SSDT_E_INVAL; }
+
+ssdt_status ssdt_save(ssdt_ctx *c, const void *base, size_t sbytes, size_t off, const int64_t *shape, int32_t ndim,
+                      int32_t dtype, ssdt_tid *out) {
+  return c ? c->save(base, sbytes, off, shape, ndim, dtype, out) : SSDT_E_INVAL;
+}
+
+ssdt_status ssdt_offload(ssdt_ctx *c, int32_t scope, ssdt_stream p) { return c ? c->offload(scope, p) : SSDT_E_INVAL; }
+ssdt_status ssdt_prefetch(ssdt_ctx *c, int32_t scope) { return c ? c->prefetch(scope) : SSDT_E_INVAL; }
+ssdt_status ssdt_get(ssdt_ctx *c, ssdt_tid t, ssdt_stream s, void **out) { return c ? c->get(t, s, out) : SSDT_E_INVAL; }
+ssdt_status ssdt_release(ssdt_ctx *c, int32_t scope, ssdt_stream s) { return c ? c->release(scope, s) : SSDT_E_INVAL; }
+
+ssdt_status ssdt_get_stats(ssdt_ctx *c, ssdt_stats *out) {
+  if (!c || !out) return SSDT_E_INVAL;
+  // fold in the wait measurements whose closing event has completed
+  for (size_t i = 0; i < c->waits.size();) {
+    WaitPair w = c->waits[i];
+    if (c->be->done(w.b)) {
+      double ms = c->be->elapsed_ms(w.a, w.b);
+      uint64_t ns = ms > 0 ? (uint64_t)(ms * 1e6) : 0;
+      (w.kind == 0 ? c->st.exposed_load_wait_ns : c->st.exposed_store_wait_ns) += ns;
+      if (--w.a->refs <= 0) c->be->recycle(w.a);
+      if (--w.b->refs <= 0) c->be->recycle(w.b);
+      c->waits[i] = c->waits.back();
+      c->waits.pop_back();
+    } else {
+      ++i;
+    }
+  }
+  c->st.arena_in_use = c->in_use;
+  c->st.arena_high_water = c->high_water;
+  c->st.arena_peak_in_use = c->peak_in_use;
+  c->st.arena_allocs = c->n_allocs;
+  *out = c->st;
+  return SSDT_OK;
+}
+
+ssdt_status ssdt_num_records(const ssdt_ctx *c, uint32_t *out) {
+  if (!c || !out) return SSDT_E_INVAL;
+  *out = (uint32_t)c->recs.size();
+  return SSDT_OK;
+}
+
+ssdt_status ssdt_get_record(const ssdt_ctx *c, uint32_t i, ssdt_record *out) {
+  if (!c || !out) return SSDT_E_INVAL;
+  if (i >= c->recs.size()) return SSDT_E_NOTFOUND;
+  const Rec &r = c->recs[i];
+  out->tid = r.tid;
+  out->layer = r.layer;
+  out->cls = r.cls;
+  out->state = r.state;
+  out->n_scopes = (int32_t)r.scopes.size();
+  out->bytes = r.bytes;
+  out->pack_offset = r.pack_offset;
+  out->pool_offset = r.pool_offset;
+  out->device_ptr = r.dev;
+  return SSDT_OK;
+}
+
+ssdt_status ssdt_pool_read(ssdt_ctx *c, size_t off, void *dst, size_t bytes) {
+  if (!c || !dst) return SSDT_E_INVAL;
+  if (off + bytes > c->cfg.pool_bytes) return c->fail(SSDT_E_INVAL, "pool_read: range outside the pool");
+  c->be->sync_io();
+  memcpy(dst, (char *)c->be->pool() + off, bytes);
+  return SSDT_OK;
+}
+
+ssdt_status ssdt_sim_complete(ssdt_ctx *c, int32_t dir, int32_t n, int32_t *done) {
+  if (!c) return SSDT_E_INVAL;
+  int k = c->be->sim_complete(dir, n);
+  if (k < 0) return c->fail(SSDT_E_UNSUPPORTED, "sim_complete: not the simulated backend");
+  if (done) *done = k;
+  return SSDT_OK;
+}
+
+ssdt_status ssdt_sync_io(ssdt_ctx *c) {
+  if (!c) return SSDT_E_INVAL;
+  c->be->sync_io();
+  c->poll();
+  return SSDT_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,328 @@
+"""Host logic of the tensor cache, exercised without a GPU through the simulated copy
+backend (copies complete when the test says so), and compared with the bookkeeping checker."""
+import ctypes
+import re
+import os
+
+import numpy as np
+import pytest
+
+from oracle import registry_oracle as ro
+from paper_2408_10013_amd import binding as sb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+class Arena:
+    def __init__(self, nbytes):
+        self.buf = np.zeros(nbytes + 256, dtype=np.uint8)
+        addr = self.buf.ctypes.data
+        self.base = (addr + 255) // 256 * 256
+        self.nbytes = nbytes
+
+    def view(self, ptr, n):
+        off = ptr - self.buf.ctypes.data
+        return self.buf[off:off + n]
+
+
+def make(arena_bytes=1 << 20, pool_bytes=1 << 20, **kw):
+    ar = Arena(arena_bytes)
+    kw.setdefault("min_offload_elems", 0)
+    kw.setdefault("keep_last", 0)
+    ctx = sb.ssdt_ctx_create(backend=sb.BACKEND_SIM, arena_base=ar.base, arena_bytes=arena_bytes,
+                             pool_bytes=pool_bytes, **kw)
+    return ctx, ar
+
+
+def records(ctx):
+    return [sb.ssdt_get_record(ctx, i) for i in range(sb.ssdt_num_records(ctx))]
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "ssdt.h")).read()
+    declared = set(re.findall(r"\b(ssdt_[a-z_0-9]+)\s*\(", hdr))
+    assert declared == set(sb.exported_symbols())
+    l = sb.lib()
+    for name in declared:
+        assert hasattr(l, name), name
+    assert "gfx950" in sb.ssdt_version()
+
+
+def test_struct_layouts_match_the_header():
+    assert ctypes.sizeof(sb.ssdt_config) == 64
+    assert ctypes.sizeof(sb.ssdt_stats) == 22 * 8
+    assert ctypes.sizeof(sb.ssdt_record) == 56
+    assert ctypes.sizeof(sb.ssdt_layer_desc) == 56
+    assert ctypes.sizeof(sb.ssdt_layer_weights) == 20 * 8
+    assert ctypes.sizeof(sb.ssdt_layer_saved) == 8 + 24 * sb.SV_COUNT
+    assert sb.SV_COUNT == 24
+
+
+def test_layer_entry_points_refuse_the_simulated_backend():
+    ctx, ar = make()
+    d = sb.make_desc(B=1, S=4, H=8, A=2, F=16)
+    with pytest.raises(sb.SsdtError) as e:
+        sb.ssdt_layer_fwd(ctx, d, sb.make_weights({}), 0, ar.base, 0, 0, ar.base, 0)
+    assert e.value.status == sb.E_UNSUPPORTED
+    sb.ssdt_ctx_destroy(ctx)
+
+
+def replay(ctx, reg, events, ptrs):
+    """events: ('begin', s) | ('end', s) | ('save', key, bytes, numel) | ('weight', key).  `ptrs` maps
+    key -> (device pointer, bytes)."""
+    out = []
+    for ev in events:
+        if ev[0] == "begin":
+            sb.ssdt_scope_begin(ctx, ev[1]); reg.scope_begin(ev[1])
+        elif ev[0] == "end":
+            sb.ssdt_scope_end(ctx, ev[1]); reg.scope_end(ev[1])
+        elif ev[0] == "weight":
+            sb.ssdt_register_weight(ctx, ptrs[ev[1]][0], ptrs[ev[1]][1]); reg.register_weight(ev[1])
+        else:
+            _, key, nbytes, numel = ev
+            got = sb.ssdt_save(ctx, ptrs[key][0], nbytes, 0, [numel], sb.F32 if numel * 4 <= nbytes else sb.BF16)
+            want = reg.save(key, nbytes, numel)
+            out.append((got, want))
+    return out
+
+
+def compare(ctx, reg):
+    st = sb.ssdt_get_stats(ctx)
+    for k, v in vars(reg.c).items():
+        assert st[k] == v, (k, st[k], v)
+    recs = records(ctx)
+    assert len(recs) == len(reg.records)
+    cls = {ro.SMALL: sb.CLS_SMALL, ro.KEPT: sb.CLS_KEPT, ro.OFFLOADED: sb.CLS_OFFLOADED}
+    for g, w in zip(recs, reg.records):
+        assert (g["tid"], g["layer"], g["cls"], g["bytes"], g["pack_offset"], g["pool_offset"], g["n_scopes"]) == \
+               (w.stamp, w.layer, cls[w.cls], w.bytes, w.pack_offset, w.pool_offset, len(w.scopes))
+
+
+def test_hand_worked_trace_matches_checker():
+    ctx, ar = make(min_offload_elems=10, budget_bytes=2000, keep_last=1)
+    sb.ssdt_step_begin(ctx, 3)
+    reg = ro.RegistryOracle(3, 10, 2000, 1, 1 << 20)
+    wbuf = np.zeros(4000, dtype=np.uint8)
+    ptrs = {"W": (wbuf.ctypes.data, 4000)}
+    for key, n in (("a", 300), ("s", 16), ("b", 1000), ("c", 600), ("d", 200), ("e", 100), ("f", 50)):
+        ptrs[key] = (sb.ssdt_arena_alloc(ctx, n), n)
+    ev = [("weight", "W"), ("begin", 0), ("save", "W", 4000, 1000), ("save", "a", 300, 150), ("save", "s", 16, 4),
+          ("save", "b", 1000, 500), ("save", "a", 300, 75), ("end", 0),
+          ("begin", 1), ("save", "c", 600, 300), ("save", "d", 200, 100), ("save", "e", 100, 50), ("end", 1),
+          ("begin", 2), ("save", "f", 50, 25), ("end", 2)]
+    pairs = replay(ctx, reg, ev, ptrs)
+    assert all(g == w for g, w in pairs), pairs
+    assert [g for g, _ in pairs] == [0, 1, 0, 3, 1, 4, 5, 6, 7]
+    compare(ctx, reg)
+    sb.ssdt_ctx_destroy(ctx)
+
+
+@pytest.mark.parametrize("arch,norm,act", [("gpt_preln", "layernorm", "gelu"), ("bert_postln", "layernorm", "gelu"),
+                                           ("t5_enc", "rmsnorm", "relu")])
+def test_layer_traces_match_checker(arch, norm, act):
+    B, S, H, A, F, e, L = 2, 16, 32, 4, 128, 2, 3
+    T = B * S
+    tr = ro.saved_trace(arch, norm, act, T, H, F, B, A, S, e)
+    for kw in (dict(min_offload_elems=0, keep_last=0, budget_bytes=-1), dict(min_offload_elems=T * H, keep_last=1, budget_bytes=-1),
+               dict(min_offload_elems=0, keep_last=0, budget_bytes=3 * T * H * e)):
+        ctx, ar = make(arena_bytes=4 << 20, pool_bytes=2 << 20, **kw)
+        sb.ssdt_step_begin(ctx, L)
+        reg = ro.RegistryOracle(L, kw["min_offload_elems"], None if kw["budget_bytes"] < 0 else kw["budget_bytes"],
+                                kw["keep_last"], 2 << 20)
+        for l in range(L):
+            ptrs, events = {}, [("begin", l)]
+            for name, storage, sbytes, numel in tr:
+                if storage not in ptrs:
+                    ptrs[storage] = (sb.ssdt_arena_alloc(ctx, sbytes), sbytes)
+                events.append(("save", storage, sbytes, numel))
+            events.append(("end", l))
+            # storages are per layer: rename keys for the checker
+            for evn in events:
+                if evn[0] == "begin": reg.scope_begin(l); sb.ssdt_scope_begin(ctx, l)
+                elif evn[0] == "end": reg.scope_end(l); sb.ssdt_scope_end(ctx, l)
+                else:
+                    _, key, nb, ne = evn
+                    dt = sb.F32 if key.startswith(("mean", "rstd", "lse")) else sb.BF16
+                    got = sb.ssdt_save(ctx, ptrs[key][0], nb, 0, [ne], dt)
+                    assert got == reg.save((l, key), nb, ne)
+        compare(ctx, reg)
+        if arch == "gpt_preln" and kw["min_offload_elems"] == 0 and kw["budget_bytes"] < 0:
+            st = sb.ssdt_get_stats(ctx)
+            assert (st["save_calls"], st["unique"], st["dedup_hits"]) == (16 * L, 13 * L, 3 * L)
+        sb.ssdt_ctx_destroy(ctx)
+
+
+def test_views_share_an_id_and_weight_views_are_excluded():
+    ctx, ar = make()
+    sb.ssdt_step_begin(ctx, 1)
+    T, H = 8, 4
+    qkv = sb.ssdt_arena_alloc(ctx, T * 3 * H * 2)
+    w = np.zeros(64, dtype=np.float32)
+    sb.ssdt_register_weight(ctx, w.ctypes.data, w.nbytes)
+    sb.ssdt_scope_begin(ctx, 0)
+    ids = [sb.ssdt_save(ctx, qkv, T * 3 * H * 2, off, [T, H], sb.BF16) for off in (0, 0, 0)]
+    # a "transposed" weight is another view of the weight's storage (Sec. 3.3.1)
+    assert sb.ssdt_save(ctx, w.ctypes.data, w.nbytes, 0, [8, 8], sb.F32) == 0
+    assert sb.ssdt_save(ctx, w.ctypes.data + 64, w.nbytes - 64, 0, [4, 4], sb.F32) == 0
+    sb.ssdt_scope_end(ctx, 0)
+    st = sb.ssdt_get_stats(ctx)
+    assert ids[0] == ids[1] == ids[2] != 0
+    assert (st["unique"], st["dedup_hits"], st["bypass_weight"], st["bytes_offloaded"]) == (1, 2, 2, T * 3 * H * 2)
+    sb.ssdt_ctx_destroy(ctx)
+
+
+def test_address_reuse_gets_a_new_stamp_and_store_completion_frees_the_slot():
+    ctx, ar = make(arena_bytes=4096)
+    sb.ssdt_step_begin(ctx, 2)
+    a = sb.ssdt_arena_alloc(ctx, 4096)
+    ar.view(a, 4096)[:] = 7
+    sb.ssdt_scope_begin(ctx, 0)
+    ta = sb.ssdt_save(ctx, a, 4096, 0, [1024], sb.F32)
+    sb.ssdt_scope_end(ctx, 0)
+    sb.ssdt_arena_free(ctx, a)                       # caller's reference gone, registry's remains
+    assert sb.ssdt_get_stats(ctx)["arena_in_use"] == 4096
+    sb.ssdt_offload(ctx, 0)
+    assert records(ctx)[0]["state"] == sb.ST_STORING
+    assert sb.ssdt_get_stats(ctx)["arena_in_use"] == 4096     # not reusable before the store completes
+    assert sb.ssdt_sim_complete(ctx, 0, 1) == 1
+    sb.ssdt_sync_io(ctx)
+    assert records(ctx)[0]["state"] == sb.ST_OFFLOADED and records(ctx)[0]["device_ptr"] is None
+    assert sb.ssdt_get_stats(ctx)["arena_in_use"] == 0
+    b = sb.ssdt_arena_alloc(ctx, 4096)
+    assert b == a                                    # same address, a different storage
+    ar.view(b, 4096)[:] = 9
+    sb.ssdt_scope_begin(ctx, 1)
+    tb = sb.ssdt_save(ctx, b, 4096, 0, [1024], sb.F32)
+    sb.ssdt_scope_end(ctx, 1)
+    assert tb == ta + 1 and sb.ssdt_get_stats(ctx)["dedup_hits"] == 0
+    assert sb.ssdt_pool_read(ctx, 0, 4096) == bytes([7]) * 4096
+    sb.ssdt_ctx_destroy(ctx)
+
+
+def test_fifo_stores_reverse_prefetch_forwarding_and_release():
+    ctx, ar = make(arena_bytes=1 << 16)
+    sb.ssdt_step_begin(ctx, 2)
+    ptrs, tids = {}, {}
+    for l, names in ((0, "abc"), (1, "de")):
+        sb.ssdt_scope_begin(ctx, l)
+        for i, n in enumerate(names):
+            p = sb.ssdt_arena_alloc(ctx, 1024)
+            ar.view(p, 1024)[:] = ord(n)
+            ptrs[n] = p
+            tids[n] = sb.ssdt_save(ctx, p, 1024, 0, [256], sb.F32)
+            sb.ssdt_arena_free(ctx, p)
+        sb.ssdt_scope_end(ctx, l)
+        sb.ssdt_offload(ctx, l)
+    # stores complete in submission order: after 2 completions exactly a and b are off the device
+    assert sb.ssdt_sim_complete(ctx, 0, 2) == 2
+    sb.ssdt_prefetch(ctx, 1)                          # d, e still being stored -> forwarded
+    s = sb.ssdt_get_stats(ctx)
+    assert s["forwarded"] == 2 and s["loads"] == 0
+    assert sb.ssdt_get(ctx, tids["d"]) == ptrs["d"] and sb.ssdt_get(ctx, tids["e"]) == ptrs["e"]
+    sb.ssdt_prefetch(ctx, 0)                          # c forwarded; b then a loaded, in that order
+    s = sb.ssdt_get_stats(ctx)
+    assert s["forwarded"] == 3 and s["loads"] == 2
+    rec = {r["tid"]: r for r in records(ctx)}
+    assert rec[tids["a"]]["state"] == sb.ST_LOADING and rec[tids["b"]]["state"] == sb.ST_LOADING
+    assert sb.ssdt_sim_complete(ctx, 1, 1) == 1       # the first load to finish is b's (reverse order)
+    pb = rec[tids["b"]]["device_ptr"]; pa = rec[tids["a"]]["device_ptr"]
+    assert bytes(ar.view(pb, 1024)) == b"b" * 1024
+    assert bytes(ar.view(pa, 1024)) != b"a" * 1024
+    assert sb.ssdt_get(ctx, tids["a"]) == pa          # get waits for the load
+    assert bytes(ar.view(pa, 1024)) == b"a" * 1024
+    # release: memory returns, later use is an error
+    before = sb.ssdt_get_stats(ctx)["arena_in_use"]
+    sb.ssdt_release(ctx, 1)
+    assert sb.ssdt_get_stats(ctx)["arena_in_use"] == before - 2048
+    with pytest.raises(sb.SsdtError) as e:
+        sb.ssdt_get(ctx, tids["d"])
+    assert e.value.status == sb.E_STATE
+    sb.ssdt_release(ctx, 0)
+    assert sb.ssdt_get_stats(ctx)["arena_in_use"] == 0 and sb.ssdt_get_stats(ctx)["released"] == 5
+    sb.ssdt_step_begin(ctx, 2)                        # a clean step can start
+    sb.ssdt_ctx_destroy(ctx)
+
+
+def test_shared_storage_released_after_its_last_scope_and_caller_reference_keeps_it():
+    ctx, ar = make(arena_bytes=1 << 16)
+    sb.ssdt_step_begin(ctx, 2)
+    enc = sb.ssdt_arena_alloc(ctx, 2048)
+    ar.view(enc, 2048)[:] = 5
+    sb.ssdt_scope_begin(ctx, 0); t0 = sb.ssdt_save(ctx, enc, 2048, 0, [512], sb.F32); sb.ssdt_scope_end(ctx, 0)
+    sb.ssdt_offload(ctx, 0)
+    sb.ssdt_sim_complete(ctx, 0, 1); sb.ssdt_sync_io(ctx)
+    # the store is done but the caller still holds the block: it must not be reused
+    assert sb.ssdt_get_stats(ctx)["arena_in_use"] == 2048
+    other = sb.ssdt_arena_alloc(ctx, 2048)
+    assert other != enc
+    sb.ssdt_scope_begin(ctx, 1); t1 = sb.ssdt_save(ctx, enc, 2048, 0, [512], sb.F32); sb.ssdt_scope_end(ctx, 1)
+    assert t1 == t0 and sb.ssdt_get_stats(ctx)["dedup_hits"] == 1 and sb.ssdt_get_stats(ctx)["bytes_offloaded"] == 2048
+    sb.ssdt_offload(ctx, 1)                           # nothing new to store
+    assert sb.ssdt_sim_complete(ctx, 0, 5) == 0
+    sb.ssdt_arena_free(ctx, enc)
+    sb.ssdt_prefetch(ctx, 0)
+    p = sb.ssdt_get(ctx, t0)
+    assert bytes(ar.view(p, 2048)) == bytes([5]) * 2048
+    sb.ssdt_release(ctx, 1)
+    assert records(ctx)[0]["state"] == sb.ST_RESIDENT and records(ctx)[0]["n_scopes"] == 1
+    sb.ssdt_release(ctx, 0)
+    assert records(ctx)[0]["state"] == sb.ST_RELEASED
+    sb.ssdt_ctx_destroy(ctx)
+
+
+def test_arena_pressure_waits_for_the_oldest_store():
+    ctx, ar = make(arena_bytes=2048)
+    sb.ssdt_step_begin(ctx, 2)
+    a = sb.ssdt_arena_alloc(ctx, 1024); ar.view(a, 1024)[:] = 1
+    b = sb.ssdt_arena_alloc(ctx, 1024); ar.view(b, 1024)[:] = 2
+    sb.ssdt_scope_begin(ctx, 0)
+    ta = sb.ssdt_save(ctx, a, 1024, 0, [256], sb.F32); tb = sb.ssdt_save(ctx, b, 1024, 0, [256], sb.F32)
+    sb.ssdt_scope_end(ctx, 0)
+    sb.ssdt_arena_free(ctx, a); sb.ssdt_arena_free(ctx, b)
+    sb.ssdt_offload(ctx, 0)
+    c = sb.ssdt_arena_alloc(ctx, 1024)                # full: waits for a's store, then reuses a's block
+    assert c == a and records(ctx)[0]["state"] == sb.ST_OFFLOADED and records(ctx)[1]["state"] == sb.ST_STORING
+    assert sb.ssdt_pool_read(ctx, 0, 1024) == bytes([1]) * 1024
+    with pytest.raises(sb.SsdtError) as e:
+        sb.ssdt_arena_alloc(ctx, 4096)
+    assert e.value.status == sb.E_NOMEM
+    sb.ssdt_ctx_destroy(ctx)
+
+
+def test_error_paths():
+    ctx, ar = make()
+    with pytest.raises(sb.SsdtError) as e:
+        sb.ssdt_scope_begin(ctx, 0)                   # no step
+    assert e.value.status == sb.E_STATE
+    sb.ssdt_step_begin(ctx, 1)
+    p = sb.ssdt_arena_alloc(ctx, 256)
+    with pytest.raises(sb.SsdtError) as e:
+        sb.ssdt_save(ctx, p, 256, 0, [64], sb.F32)    # outside a scope
+    assert e.value.status == sb.E_STATE
+    sb.ssdt_scope_begin(ctx, 0)
+    with pytest.raises(sb.SsdtError) as e:
+        sb.ssdt_save(ctx, p, 256, 0, [65], sb.F32)    # view larger than storage
+    assert e.value.status == sb.E_INVAL
+    with pytest.raises(sb.SsdtError) as e:
+        sb.ssdt_scope_end(ctx, 3)
+    assert e.value.status == sb.E_STATE
+    assert sb.ssdt_get_stats(ctx)["save_calls"] == 0  # failed calls left no trace
+    t = sb.ssdt_save(ctx, p, 256, 0, [64], sb.F32)
+    sb.ssdt_scope_end(ctx, 0)
+    with pytest.raises(sb.SsdtError) as e:
+        sb.ssdt_get(ctx, 999)
+    assert e.value.status == sb.E_NOTFOUND
+    with pytest.raises(sb.SsdtError) as e:
+        sb.ssdt_step_begin(ctx, 1)                    # previous step not released
+    assert e.value.status == sb.E_STATE
+    with pytest.raises(sb.SsdtError) as e:
+        sb.ssdt_arena_free(ctx, p + 64)
+    assert e.value.status == sb.E_STATE
+    sb.ssdt_release(ctx, 0)
+    sb.ssdt_ctx_destroy(ctx)
+    with pytest.raises(sb.SsdtError) as e:
+        sb.ssdt_ctx_create(backend=sb.BACKEND_SIM, arena_base=ar.base + 8, arena_bytes=1024)
+    assert e.value.status == sb.E_INVAL
+    with pytest.raises(sb.SsdtError) as e:
+        sb.ssdt_ctx_create(backend=sb.BACKEND_SIM, spill_path="/tmp/x")
+    assert e.value.status == sb.E_UNSUPPORTED
