@@ -1,0 +1,94 @@
+// Internal: launchers of the layer's HIP kernels.  All pointers are device pointers, all
+// matrices row-major; element type is float or bf16 (SSDT_F32 / SSDT_BF16) with fp32
+// arithmetic and accumulation throughout.  Every reduction runs in a fixed order, so results
+// do not depend on addresses or timing.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "ssdt.h"
+
+namespace ssdt {
+namespace k {
+
+enum Epi {
+  EPI_NONE = 0,    // C = acc
+  EPI_BIAS,        // C = acc + bias
+  EPI_BIAS_ACT,    // u = acc + bias; C = u (skipped when C is null); C2 = act(u)
+  EPI_BIAS_RESID,  // C = acc + bias + resid
+  EPI_ACTBWD       // C = acc * act'(aux)   (aux = pre-activation for GELU, activation output for ReLU)
+};
+
+// C[M,N] = sum_k A(m,k) B(k,n)   with   A(m,k) = transA ? A[k*lda+m] : A[m*lda+k]
+//                                       B(k,n) = transB ? B[n*ldb+k] : B[k*ldb+n]
+struct Gemm {
+  int M = 0, N = 0, K = 0;
+  const void *A = nullptr;
+  long lda = 0;
+  bool transA = false;
+  const void *B = nullptr;
+  long ldb = 0;
+  bool transB = false;
+  void *C = nullptr;
+  long ldc = 0;
+  int epi = EPI_NONE;
+  const void *bias = nullptr;   // [N] or null (then treated as 0)
+  const void *resid = nullptr;  // [M, ldr]
+  long ldr = 0;
+  void *C2 = nullptr;           // [M, ldc]
+  const void *aux = nullptr;    // [M, ldc]
+  int act = SSDT_ACT_GELU;
+  int dtype = SSDT_F32;
+  void *scratch = nullptr;      // optional: room for transposed copies of operands (bf16 fast path)
+  size_t scratch_bytes = 0;
+};
+hipError_t gemm(const Gemm &g, hipStream_t s);
+// scratch bytes gemm() can make use of for this problem (0 for fp32)
+size_t gemm_scratch_bytes(int M, int N, int K, bool transA, bool transB, int dtype);
+
+// Row norm over H.  kind = SSDT_NORM_*.  mean may be null for RMSNorm.
+hipError_t norm_fwd(const void *x, const void *gamma, const void *beta, void *y, float *mean, float *rstd, int rows,
+                    int H, float eps, int kind, int dtype, hipStream_t s);
+// dx = (resid ? resid : 0) + norm-backward(dy); dgamma/dbeta by a two-stage column reduction
+// through `partial` (fp32, colreduce_partial_floats(rows, H) elements).
+hipError_t norm_bwd(const void *dy, const void *x, const float *mean, const float *rstd, const void *gamma,
+                    const void *resid, void *dx, void *dgamma, void *dbeta, float *partial, int rows, int H, int kind,
+                    int dtype, hipStream_t s);
+// out[n] = sum_m a[m, n]  (bias gradients), same two-stage scheme
+hipError_t colsum(const void *a, long lda, void *out, float *partial, int rows, int cols, int dtype, hipStream_t s);
+size_t colreduce_partial_floats(int rows, int cols);
+
+struct Attn {
+  int B = 0, A = 0, Sq = 0, Sk = 0, d = 0;
+  float scale = 1.f;
+  int mask = SSDT_MASK_NONE;
+  const int32_t *kv_len = nullptr;  // [B], key-padding mask only
+  int dtype = SSDT_F32;
+  const void *q = nullptr, *k = nullptr, *v = nullptr;  // rows b*S + i, head h at columns h*d
+  long ldq = 0, ldk = 0, ldv = 0;
+  void *o = nullptr;
+  long ldo = 0;
+  float *lse = nullptr;  // [B, A, Sq]
+  // backward only
+  const void *dout = nullptr;
+  long lddo = 0;
+  void *dq = nullptr, *dk = nullptr, *dv = nullptr;
+  long lddq = 0, lddk = 0, lddv = 0;
+  float *delta = nullptr;  // scratch [B, A, Sq]
+};
+hipError_t attn_fwd(const Attn &a, hipStream_t s);
+hipError_t attn_bwd(const Attn &a, hipStream_t s);
+
+// out[c, r] = in[r, c]
+hipError_t transpose(const void *in, long ldi, void *out, long ldo, int rows, int cols, int dtype, hipStream_t s);
+// y += x  (elementwise, n elements)
+hipError_t add_inplace(void *y, const void *x, size_t n, int dtype, hipStream_t s);
+
+// fast paths (bf16 on the matrix cores); return hipErrorNotSupported when the shape does not fit
+hipError_t gemm_mfma_bf16(const Gemm &g, hipStream_t s);
+hipError_t attn_fwd_mfma_bf16(const Attn &a, hipStream_t s);
+hipError_t attn_bwd_mfma_bf16(const Attn &a, hipStream_t s);
+
+}  // namespace k
+}  // namespace ssdt
