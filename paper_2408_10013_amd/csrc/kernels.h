@@ -44,6 +44,8 @@ struct Gemm {
   size_t scratch_bytes = 0;
 };
 hipError_t gemm(const Gemm &g, hipStream_t s);
+hipError_t gemm_generic(const Gemm &g, hipStream_t s);  // the FMA kernel, any shape (gemm() falls back to it)
+extern int g_force_tile;                                // 0 = choose; 128 / 256 pin the matrix-core tile
 // scratch bytes gemm() can make use of for this problem (0 for fp32)
 size_t gemm_scratch_bytes(int M, int N, int K, bool transA, bool transB, int dtype);
 
@@ -79,6 +81,10 @@ struct Attn {
 };
 hipError_t attn_fwd(const Attn &a, hipStream_t s);
 hipError_t attn_bwd(const Attn &a, hipStream_t s);
+// the one-wavefront-per-row kernels, any shape (attn_fwd / attn_bwd fall back to them)
+hipError_t attn_fwd_generic(const Attn &a, hipStream_t s);
+hipError_t attn_bwd_generic(const Attn &a, hipStream_t s);
+hipError_t attn_delta(const Attn &a, hipStream_t s);  // delta[b,h,i] = sum_c o[i,c] dout[i,c]
 
 // out[c, r] = in[r, c]
 hipError_t transpose(const void *in, long ldi, void *out, long ldo, int rows, int cols, int dtype, hipStream_t s);

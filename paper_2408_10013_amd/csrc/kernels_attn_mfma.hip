@@ -1,0 +1,429 @@
+// Fused scaled-dot-product attention on the CDNA4 matrix cores (bf16 in, fp32 softmax and
+// accumulation): forward with an online softmax over LDS-resident K/V tiles, and a
+// deterministic backward in two kernels (dK/dV per key block, dQ per query block) that
+// recompute the probabilities tile by tile from the saved log-sum-exp, so that no S x S
+// tensor is ever stored (the property the paper relies on when it counts saved activations,
+// Sec. 4.3) and no floating-point atomics are needed.
+//
+// All matrix products use v_mfma_f32_32x32x16_bf16.  Scores are produced transposed
+// (keys x queries) so that every lane owns one query column: the row maximum and sum of the
+// softmax are in-lane reductions plus one exchange with lane^32, and the rescaling of the
+// output accumulator is in-lane.  Operands that are needed "k-major" (V in P.V, K in dS.K,
+// Q and dO in the key-side gradients) stay row-major in LDS and are fetched with the
+// transposing LDS read (ds_read_b64_tr_b16), so no transposed copies are made.
+#include "dev.h"
+#include "kernels.h"
+
+namespace ssdt {
+namespace k {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4_t;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4_t;
+typedef __attribute__((address_space(3))) s16x4_t lds_s16x4_t;
+
+struct FaP {
+  int B, A, Sq, Sk, mask;
+  float scale;
+  const int32_t *kv_len;
+  const uint16_t *q, *k, *v, *o, *dout;
+  uint16_t *out, *dq, *dk, *dv;
+  float *lse;
+  const float *delta;
+  long ldq, ldk, ldv, ldo, lddo, lddq, lddk, lddv;
+};
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// 8 bf16 for an MFMA operand taken from a k-major LDS tile T[k][i] (row stride ld elements):
+// lane (i = lane % 32) receives T[k_lo + 0..3][i0 + i] and T[k_hi + 0..3][i0 + i].
+// ds_read_b64_tr_b16 works on groups of 16 lanes: lane L of a group supplies the 4 elements at
+// its address and receives element (L % 4) of the lanes 4j + L/4, j = 0..3.
+__device__ __forceinline__ bf16x8_t frag_tr(const uint16_t *T, int ld, int k_lo, int k_hi, int i0, int lane) {
+  const int L = lane & 15, n0 = i0 + ((lane >> 4) & 1) * 16 + 4 * (L & 3), kr = L >> 2;
+  s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)(T + (k_lo + kr) * ld + n0));
+  s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)(T + (k_hi + kr) * ld + n0));
+  union { struct { s16x4_t a, b; } s; bf16x8_t v; } u;
+  u.s.a = lo;
+  u.s.b = hi;
+  return u.v;
+}
+
+__device__ __forceinline__ bf16x8_t pack8(const float *a, const float *b) {
+  union { uint32_t w[4]; bf16x8_t v; } u;
+  u.w[0] = pack_bf2(a[0], a[1]); u.w[1] = pack_bf2(a[2], a[3]);
+  u.w[2] = pack_bf2(b[0], b[1]); u.w[3] = pack_bf2(b[2], b[3]);
+  return u.v;
+}
+
+// copies ROWS x D bf16 (row stride ld in global memory) into LDS with row stride LDS_LD; rows at or
+// beyond `valid` are zero-filled
+template <int D, int ROWS, int LDS_LD>
+__device__ __forceinline__ void load_tile(const uint16_t *g, long ld, int valid, uint16_t *s, int tid) {
+  constexpr int CPR = D / 8, N = ROWS * CPR / 256;
+#pragma unroll
+  for (int i = 0; i < N; ++i) {
+    int c = tid + i * 256, row = c / CPR, kc = c % CPR;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (row < valid) v = *(const uint4 *)(g + (long)row * ld + kc * 8);
+    *(uint4 *)(s + row * LDS_LD + kc * 8) = v;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// forward: one workgroup = 128 queries of one (sequence, head); each wavefront 32 queries
+// ------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256, 2) void fa_fwd_k(FaP p) {
+  constexpr int BKV = 64, LK = D + 8, LV = D + 16, KS = D / 16, DB = D / 32;
+  __shared__ __attribute__((aligned(16))) uint16_t sK[BKV * LK];
+  __shared__ __attribute__((aligned(16))) uint16_t sV[BKV * LV];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, half = lane >> 5, li = lane & 31;
+  const int nqb = p.Sq / 128;
+  const int qb = (p.mask == SSDT_MASK_CAUSAL) ? nqb - 1 - (int)blockIdx.x : (int)blockIdx.x;  // long rows first
+  const int h = blockIdx.y, b = blockIdx.z;
+  const int q0 = qb * 128 + w * 32, qi = q0 + li;
+  const uint16_t *qp = p.q + (long)(b * p.Sq + qi) * p.ldq + h * D;
+  bf16x8_t qf[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) qf[ks] = *(const bf16x8_t *)(qp + ks * 16 + half * 8);
+  int limit = p.Sk;
+  if (p.mask == SSDT_MASK_CAUSAL) limit = min(limit, qb * 128 + 128);
+  if (p.mask == SSDT_MASK_KEYPAD) limit = min(limit, max(0, p.kv_len[b]));
+  const int ntiles = (limit + BKV - 1) / BKV;
+  const float sc = p.scale * kLog2e;
+  float m = -INFINITY, l = 0.f;
+  f32x16_t oacc[DB];
+#pragma unroll
+  for (int d = 0; d < DB; ++d)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) oacc[d][r] = 0.f;
+  const uint16_t *kg = p.k + (long)b * p.Sk * p.ldk + h * D, *vg = p.v + (long)b * p.Sk * p.ldv + h * D;
+
+  for (int t = 0; t < ntiles; ++t) {
+    const int j0 = t * BKV;
+    __syncthreads();
+    load_tile<D, BKV, LK>(kg + (long)j0 * p.ldk, p.ldk, p.Sk - j0, sK, tid);
+    load_tile<D, BKV, LV>(vg + (long)j0 * p.ldv, p.ldv, p.Sk - j0, sV, tid);
+    __syncthreads();
+    if (p.mask == SSDT_MASK_CAUSAL && j0 > q0 + 31) continue;  // tile entirely above this wavefront's diagonal
+    f32x16_t sacc[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sacc[kb][r] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+        bf16x8_t kf = *(const bf16x8_t *)(sK + (kb * 32 + li) * LK + ks * 16 + half * 8);
+        sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc[kb], 0, 0, 0);
+      }
+    // scale, mask, online softmax (this lane: query qi, keys j0 + kb*32 + (r/4)*8 + half*4 + r%4)
+    const bool need_mask = (p.mask == SSDT_MASK_CAUSAL && j0 + BKV - 1 > q0) || (j0 + BKV > limit);
+    float mloc = -INFINITY;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float s = sacc[kb][r] * sc;
+        if (need_mask) {
+          int key = j0 + kb * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
+          if (key >= limit || (p.mask == SSDT_MASK_CAUSAL && key > qi)) s = -INFINITY;
+        }
+        sacc[kb][r] = s;
+        mloc = fmaxf(mloc, s);
+      }
+    mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
+    const float mnew = fmaxf(m, mloc), msafe = (mnew == -INFINITY) ? 0.f : mnew;
+    const float corr = exp2f(m - msafe);
+    float lsum = 0.f;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float e = exp2f(sacc[kb][r] - msafe);
+        sacc[kb][r] = e;
+        lsum += e;
+      }
+    lsum += __shfl_xor(lsum, 32, 64);
+    l = l * corr + lsum;
+    m = mnew;
+#pragma unroll
+    for (int d = 0; d < DB; ++d)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) oacc[d][r] *= corr;
+    // O^T += V^T P^T, 16 keys per step
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4) {
+      const int kb = s4 >> 1, g = (s4 & 1) * 2;
+      float pa[4] = {sacc[kb][g * 4 + 0], sacc[kb][g * 4 + 1], sacc[kb][g * 4 + 2], sacc[kb][g * 4 + 3]};
+      float pb[4] = {sacc[kb][g * 4 + 4], sacc[kb][g * 4 + 5], sacc[kb][g * 4 + 6], sacc[kb][g * 4 + 7]};
+      bf16x8_t pf = pack8(pa, pb);
+#pragma unroll
+      for (int d = 0; d < DB; ++d) {
+        bf16x8_t vf = frag_tr(sV, LV, s4 * 16 + half * 4, s4 * 16 + 8 + half * 4, d * 32, lane);
+        oacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, oacc[d], 0, 0, 0);
+      }
+    }
+  }
+  const float inv = l > 0.f ? 1.f / l : 0.f;
+  uint16_t *op = p.out + (long)(b * p.Sq + qi) * p.ldo + h * D;
+#pragma unroll
+  for (int d = 0; d < DB; ++d)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      uint2 v = make_uint2(pack_bf2(oacc[d][g * 4 + 0] * inv, oacc[d][g * 4 + 1] * inv),
+                           pack_bf2(oacc[d][g * 4 + 2] * inv, oacc[d][g * 4 + 3] * inv));
+      *(uint2 *)(op + d * 32 + g * 8 + half * 4) = v;
+    }
+  if (half == 0) p.lse[((long)b * p.A + h) * p.Sq + qi] = l > 0.f ? m * kLn2 + logf(l) : -INFINITY;
+}
+
+static bool fa_supported(const Attn &a) {
+  if (a.dtype != SSDT_BF16 || (a.d != 64 && a.d != 128)) return false;
+  if (a.Sq % 128 || a.Sk % 128) return false;
+  auto al = [](const void *p) { return ((uintptr_t)p & 15) == 0; };
+  if (!al(a.q) || !al(a.k) || !al(a.v) || a.ldq % 8 || a.ldk % 8 || a.ldv % 8) return false;
+  return true;
+}
+
+static FaP to_fa(const Attn &a) {
+  FaP p;
+  p.B = a.B; p.A = a.A; p.Sq = a.Sq; p.Sk = a.Sk; p.mask = a.mask; p.scale = a.scale; p.kv_len = a.kv_len;
+  p.q = (const uint16_t *)a.q; p.k = (const uint16_t *)a.k; p.v = (const uint16_t *)a.v; p.o = (const uint16_t *)a.o;
+  p.dout = (const uint16_t *)a.dout; p.out = (uint16_t *)a.o; p.dq = (uint16_t *)a.dq; p.dk = (uint16_t *)a.dk;
+  p.dv = (uint16_t *)a.dv; p.lse = a.lse; p.delta = a.delta;
+  p.ldq = a.ldq; p.ldk = a.ldk; p.ldv = a.ldv; p.ldo = a.ldo; p.lddo = a.lddo; p.lddq = a.lddq; p.lddk = a.lddk; p.lddv = a.lddv;
+  return p;
+}
+
+hipError_t attn_fwd_mfma_bf16(const Attn &a, hipStream_t s) {
+  if (!fa_supported(a) || ((uintptr_t)a.o & 7) || a.ldo % 4) return hipErrorNotSupported;
+  if (a.mask == SSDT_MASK_CAUSAL && a.Sq != a.Sk) return hipErrorNotSupported;
+  FaP p = to_fa(a);
+  dim3 grid(a.Sq / 128, a.A, a.B);
+  if (a.d == 128) hipLaunchKernelGGL(fa_fwd_k<128>, grid, dim3(256), 0, s, p);
+  else hipLaunchKernelGGL(fa_fwd_k<64>, grid, dim3(256), 0, s, p);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// backward, key side: one workgroup = 128 keys of one (sequence, head), each wavefront 32 keys;
+// loops over 64-query tiles of Q and dO.  dK[j] = scale sum_i dS_ij q_i, dV[j] = sum_i P_ij dO_i.
+// ------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256, 2) void fa_bwd_dkv_k(FaP p) {
+  constexpr int BQ = 64, LQ = D + 8, KS = D / 16, DB = D / 32;
+  __shared__ __attribute__((aligned(16))) uint16_t sQ[BQ * LQ];
+  __shared__ __attribute__((aligned(16))) uint16_t sdO[BQ * LQ];
+  __shared__ __attribute__((aligned(16))) float sLse[BQ], sDelta[BQ];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, half = lane >> 5, li = lane & 31;
+  const int h = blockIdx.y, b = blockIdx.z;
+  const int k0 = blockIdx.x * 128 + w * 32, kj = k0 + li;
+  int limit = p.Sk;
+  if (p.mask == SSDT_MASK_KEYPAD) limit = min(limit, max(0, p.kv_len[b]));
+  const uint16_t *kp = p.k + (long)(b * p.Sk + kj) * p.ldk + h * D, *vp = p.v + (long)(b * p.Sk + kj) * p.ldv + h * D;
+  bf16x8_t kf[KS], vf[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    kf[ks] = *(const bf16x8_t *)(kp + ks * 16 + half * 8);
+    vf[ks] = *(const bf16x8_t *)(vp + ks * 16 + half * 8);
+  }
+  f32x16_t dkacc[DB], dvacc[DB];
+#pragma unroll
+  for (int d = 0; d < DB; ++d)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { dkacc[d][r] = 0.f; dvacc[d][r] = 0.f; }
+  const float sc = p.scale * kLog2e;
+  const uint16_t *qg = p.q + (long)b * p.Sq * p.ldq + h * D, *dog = p.dout + (long)b * p.Sq * p.lddo + h * D;
+  const float *lse_g = p.lse + ((long)b * p.A + h) * p.Sq, *delta_g = p.delta + ((long)b * p.A + h) * p.Sq;
+  const int nt = p.Sq / BQ;
+  const int t0 = (p.mask == SSDT_MASK_CAUSAL) ? (int)(blockIdx.x * 128) / BQ : 0;
+  const bool block_live = (int)(blockIdx.x * 128) < limit;
+
+  for (int t = block_live ? t0 : nt; t < nt; ++t) {
+    const int i0 = t * BQ;
+    __syncthreads();
+    load_tile<D, BQ, LQ>(qg + (long)i0 * p.ldq, p.ldq, BQ, sQ, tid);
+    load_tile<D, BQ, LQ>(dog + (long)i0 * p.lddo, p.lddo, BQ, sdO, tid);
+    if (tid < BQ) sLse[tid] = lse_g[i0 + tid];
+    else if (tid < 2 * BQ) sDelta[tid - BQ] = delta_g[i0 + tid - BQ];
+    __syncthreads();
+    if (p.mask == SSDT_MASK_CAUSAL && i0 + BQ - 1 < k0) continue;  // every query of the tile precedes this wavefront's keys
+    const bool need_mask = (p.mask == SSDT_MASK_CAUSAL && i0 < k0 + 31) || (k0 + 32 > limit);
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      f32x16_t sacc, dpacc;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { sacc[r] = 0.f; dpacc[r] = 0.f; }
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        bf16x8_t qa = *(const bf16x8_t *)(sQ + (qb * 32 + li) * LQ + ks * 16 + half * 8);
+        bf16x8_t da = *(const bf16x8_t *)(sdO + (qb * 32 + li) * LQ + ks * 16 + half * 8);
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kf[ks], sacc, 0, 0, 0);
+        dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(da, vf[ks], dpacc, 0, 0, 0);
+      }
+      // this lane: key kj, queries i0 + qb*32 + g*8 + half*4 + 0..3
+      float pv[16], dsv[16];
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int qo = qb * 32 + g * 8 + half * 4;
+        const float4 l4 = *(const float4 *)(sLse + qo), d4 = *(const float4 *)(sDelta + qo);
+        const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dv[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int r = g * 4 + e;
+          float pe = exp2f(sacc[r] * sc - lv[e] * kLog2e);
+          bool dead = lv[e] == -INFINITY;
+          if (need_mask) dead = dead || kj >= limit || (p.mask == SSDT_MASK_CAUSAL && kj > i0 + qo + e);
+          pe = dead ? 0.f : pe;
+          pv[r] = pe;
+          dsv[r] = pe * (dpacc[r] - dv[e]);
+        }
+      }
+#pragma unroll
+      for (int gs = 0; gs < 2; ++gs) {
+        bf16x8_t pf = pack8(pv + gs * 8, pv + gs * 8 + 4), dsf = pack8(dsv + gs * 8, dsv + gs * 8 + 4);
+        const int klo = qb * 32 + gs * 16 + half * 4;
+#pragma unroll
+        for (int d = 0; d < DB; ++d) {
+          bf16x8_t dot = frag_tr(sdO, LQ, klo, klo + 8, d * 32, lane);
+          dvacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dot, pf, dvacc[d], 0, 0, 0);
+          bf16x8_t qt = frag_tr(sQ, LQ, klo, klo + 8, d * 32, lane);
+          dkacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qt, dsf, dkacc[d], 0, 0, 0);
+        }
+      }
+    }
+  }
+  uint16_t *dkp = p.dk + (long)(b * p.Sk + kj) * p.lddk + h * D, *dvp = p.dv + (long)(b * p.Sk + kj) * p.lddv + h * D;
+#pragma unroll
+  for (int d = 0; d < DB; ++d)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int o = d * 32 + g * 8 + half * 4;
+      *(uint2 *)(dkp + o) = make_uint2(pack_bf2(dkacc[d][g * 4 + 0] * p.scale, dkacc[d][g * 4 + 1] * p.scale),
+                                       pack_bf2(dkacc[d][g * 4 + 2] * p.scale, dkacc[d][g * 4 + 3] * p.scale));
+      *(uint2 *)(dvp + o) = make_uint2(pack_bf2(dvacc[d][g * 4 + 0], dvacc[d][g * 4 + 1]),
+                                       pack_bf2(dvacc[d][g * 4 + 2], dvacc[d][g * 4 + 3]));
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// backward, query side: one workgroup = 128 queries, each wavefront 32; loops over 64-key tiles.
+// dQ[i] = scale sum_j dS_ij k_j, accumulated in registers in a fixed order (no atomics).
+// ------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256, 2) void fa_bwd_dq_k(FaP p) {
+  constexpr int BKV = 64, LK = D + 8, KS = D / 16, DB = D / 32;
+  __shared__ __attribute__((aligned(16))) uint16_t sK[BKV * LK];
+  __shared__ __attribute__((aligned(16))) uint16_t sV[BKV * LK];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, half = lane >> 5, li = lane & 31;
+  const int nqb = p.Sq / 128;
+  const int qb = (p.mask == SSDT_MASK_CAUSAL) ? nqb - 1 - (int)blockIdx.x : (int)blockIdx.x;
+  const int h = blockIdx.y, b = blockIdx.z;
+  const int q0 = qb * 128 + w * 32, qi = q0 + li;
+  const uint16_t *qp = p.q + (long)(b * p.Sq + qi) * p.ldq + h * D, *dop = p.dout + (long)(b * p.Sq + qi) * p.lddo + h * D;
+  bf16x8_t qf[KS], dof[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    qf[ks] = *(const bf16x8_t *)(qp + ks * 16 + half * 8);
+    dof[ks] = *(const bf16x8_t *)(dop + ks * 16 + half * 8);
+  }
+  const long si = ((long)b * p.A + h) * p.Sq + qi;
+  const float lse = p.lse[si], delta = p.delta[si];
+  const bool row_dead = lse == -INFINITY;
+  const float lse2 = row_dead ? 0.f : lse * kLog2e;
+  int limit = p.Sk;
+  if (p.mask == SSDT_MASK_CAUSAL) limit = min(limit, qb * 128 + 128);
+  if (p.mask == SSDT_MASK_KEYPAD) limit = min(limit, max(0, p.kv_len[b]));
+  const int ntiles = (limit + BKV - 1) / BKV;
+  const float sc = p.scale * kLog2e;
+  f32x16_t dqacc[DB];
+#pragma unroll
+  for (int d = 0; d < DB; ++d)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) dqacc[d][r] = 0.f;
+  const uint16_t *kg = p.k + (long)b * p.Sk * p.ldk + h * D, *vg = p.v + (long)b * p.Sk * p.ldv + h * D;
+
+  for (int t = 0; t < ntiles; ++t) {
+    const int j0 = t * BKV;
+    __syncthreads();
+    load_tile<D, BKV, LK>(kg + (long)j0 * p.ldk, p.ldk, p.Sk - j0, sK, tid);
+    load_tile<D, BKV, LK>(vg + (long)j0 * p.ldv, p.ldv, p.Sk - j0, sV, tid);
+    __syncthreads();
+    if (p.mask == SSDT_MASK_CAUSAL && j0 > q0 + 31) continue;
+    const bool need_mask = (p.mask == SSDT_MASK_CAUSAL && j0 + BKV - 1 > q0) || (j0 + BKV > limit);
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      f32x16_t sacc, dpacc;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { sacc[r] = 0.f; dpacc[r] = 0.f; }
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        bf16x8_t ka = *(const bf16x8_t *)(sK + (kb * 32 + li) * LK + ks * 16 + half * 8);
+        bf16x8_t va = *(const bf16x8_t *)(sV + (kb * 32 + li) * LK + ks * 16 + half * 8);
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[ks], sacc, 0, 0, 0);
+        dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, dof[ks], dpacc, 0, 0, 0);
+      }
+      float dsv[16];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float pe = exp2f(sacc[r] * sc - lse2);
+        bool dead = row_dead;
+        if (need_mask) {
+          const int key = j0 + kb * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
+          dead = dead || key >= limit || (p.mask == SSDT_MASK_CAUSAL && key > qi);
+        }
+        pe = dead ? 0.f : pe;
+        dsv[r] = pe * (dpacc[r] - delta);
+      }
+#pragma unroll
+      for (int gs = 0; gs < 2; ++gs) {
+        bf16x8_t dsf = pack8(dsv + gs * 8, dsv + gs * 8 + 4);
+        const int klo = kb * 32 + gs * 16 + half * 4;
+#pragma unroll
+        for (int d = 0; d < DB; ++d) {
+          bf16x8_t kt = frag_tr(sK, LK, klo, klo + 8, d * 32, lane);
+          dqacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kt, dsf, dqacc[d], 0, 0, 0);
+        }
+      }
+    }
+  }
+  uint16_t *dqp = p.dq + (long)(b * p.Sq + qi) * p.lddq + h * D;
+#pragma unroll
+  for (int d = 0; d < DB; ++d)
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+      *(uint2 *)(dqp + d * 32 + g * 8 + half * 4) =
+          make_uint2(pack_bf2(dqacc[d][g * 4 + 0] * p.scale, dqacc[d][g * 4 + 1] * p.scale),
+                     pack_bf2(dqacc[d][g * 4 + 2] * p.scale, dqacc[d][g * 4 + 3] * p.scale));
+}
+
+hipError_t attn_bwd_mfma_bf16(const Attn &a, hipStream_t s) {
+  if (!fa_supported(a)) return hipErrorNotSupported;
+  if (a.mask == SSDT_MASK_CAUSAL && a.Sq != a.Sk) return hipErrorNotSupported;
+  auto al16 = [](const void *p) { return ((uintptr_t)p & 15) == 0; };
+  auto al8 = [](const void *p) { return ((uintptr_t)p & 7) == 0; };
+  if (!al16(a.dout) || a.lddo % 8 || !al8(a.dq) || !al8(a.dk) || !al8(a.dv) || a.lddq % 4 || a.lddk % 4 || a.lddv % 4 ||
+      !a.delta || !a.lse || !a.o)
+    return hipErrorNotSupported;
+  hipError_t e = attn_delta(a, s);
+  if (e != hipSuccess) return e;
+  FaP p = to_fa(a);
+  dim3 gk(a.Sk / 128, a.A, a.B), gq(a.Sq / 128, a.A, a.B);
+  if (a.d == 128) {
+    hipLaunchKernelGGL(fa_bwd_dkv_k<128>, gk, dim3(256), 0, s, p);
+    hipLaunchKernelGGL(fa_bwd_dq_k<128>, gq, dim3(256), 0, s, p);
+  } else {
+    hipLaunchKernelGGL(fa_bwd_dkv_k<64>, gk, dim3(256), 0, s, p);
+    hipLaunchKernelGGL(fa_bwd_dq_k<64>, gq, dim3(256), 0, s, p);
+  }
+  return hipGetLastError();
+}
+
+
+}  // namespace k
+}  // namespace ssdt

@@ -107,7 +107,7 @@ __global__ __launch_bounds__(256) void gemm_generic_k(GemmP p) {
   }
 }
 
-static hipError_t gemm_generic(const Gemm &g, hipStream_t s) {
+hipError_t gemm_generic(const Gemm &g, hipStream_t s) {
   GemmP p{g.M, g.N, g.K, g.A, g.B, g.C, g.C2, g.bias, g.resid, g.aux, g.lda, g.ldb, g.ldc, g.ldr,
           g.transA, g.transB, g.epi, g.act};
   dim3 grid((g.N + 63) / 64, (g.M + 63) / 64);
@@ -498,6 +498,10 @@ hipError_t attn_fwd(const Attn &a, hipStream_t s) {
     hipError_t e = attn_fwd_mfma_bf16(a, s);
     if (e != hipErrorNotSupported) return e;
   }
+  return attn_fwd_generic(a, s);
+}
+
+hipError_t attn_fwd_generic(const Attn &a, hipStream_t s) {
   AttnP p = to_p(a);
   dim3 grid((a.Sq + 3) / 4, a.A, a.B);
   if (a.dtype == SSDT_F32) hipLaunchKernelGGL(attn_fwd_generic_k<float>, grid, dim3(256), 0, s, p);
@@ -513,6 +517,19 @@ hipError_t attn_bwd(const Attn &a, hipStream_t s) {
     hipError_t e = attn_bwd_mfma_bf16(a, s);
     if (e != hipErrorNotSupported) return e;
   }
+  return attn_bwd_generic(a, s);
+}
+
+hipError_t attn_delta(const Attn &a, hipStream_t s) {
+  AttnP p = to_p(a);
+  dim3 gq((a.Sq + 3) / 4, a.A, a.B);
+  if (a.dtype == SSDT_F32) hipLaunchKernelGGL(attn_delta_k<float>, gq, dim3(256), 0, s, p);
+  else hipLaunchKernelGGL(attn_delta_k<bf16>, gq, dim3(256), 0, s, p);
+  SSDT_LAUNCH_CHECK();
+  return hipSuccess;
+}
+
+hipError_t attn_bwd_generic(const Attn &a, hipStream_t s) {
   AttnP p = to_p(a);
   dim3 gq((a.Sq + 3) / 4, a.A, a.B), gk((a.Sk + 3) / 4, a.A, a.B);
   if (a.dtype == SSDT_F32) {

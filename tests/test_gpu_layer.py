@@ -136,6 +136,11 @@ VARIANTS = {
     "t5_enc": dict(arch="t5_enc", B=2, S=65, H=128, A=2, F=192, act="relu", norm="rmsnorm", mask="none", has_bias=False, eps=1e-6),
     "t5_dec": dict(arch="t5_dec", B=2, S=33, S_kv=75, H=128, A=2, F=192, act="relu", norm="rmsnorm", mask="causal", has_bias=False, eps=1e-6),
     "gpt_d128": dict(arch="gpt_preln", B=1, S=130, H=256, A=2, F=512, act="gelu", norm="layernorm", mask="causal", has_bias=True, eps=1e-5),
+    # shapes the matrix-core kernels take (multiples of 128; head size 64 / 128)
+    "gpt_mfma": dict(arch="gpt_preln", B=2, S=256, H=256, A=2, F=1024, act="gelu", norm="layernorm", mask="causal", has_bias=True, eps=1e-5),
+    "bert_mfma": dict(arch="bert_postln", B=3, S=128, H=256, A=4, F=512, act="gelu", norm="layernorm", mask="keypad", has_bias=True, eps=1e-5),
+    "t5enc_mfma": dict(arch="t5_enc", B=2, S=128, H=128, A=2, F=384, act="relu", norm="rmsnorm", mask="none", has_bias=False, eps=1e-6),
+    "t5dec_mfma": dict(arch="t5_dec", B=2, S=128, S_kv=256, H=128, A=2, F=256, act="relu", norm="rmsnorm", mask="causal", has_bias=False, eps=1e-6),
 }
 
 
