@@ -1,0 +1,239 @@
+#!/usr/bin/env python3
+"""Benchmark of the layer forward+backward with activation offloading on one MI355X.
+
+A step = forward then backward of the whole layer stack over one micro-batch of seeded
+synthetic tensors (inputs resident in HBM), including every offload, prefetch and release.
+Three modes are timed back to back with the same context and arena:
+  off     offload amount 0: every saved tensor stays on the device
+  all     every saved tensor of every layer but the last is offloaded and prefetched back
+  budget  the offload amount is set from the measured link rate so that the I/O hides
+          behind compute (the paper's adaptive offload amount, Sec. 3.1); the headline value
+The JSON line printed at the end carries the headline (budget mode), the other two modes,
+the roofline of the dominant kernel (timed with HIP events on its launch stream inside the
+timed region) and the CPU checker timed on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16
+HOST_LINK_PEAK_GBPS = 64.0          # PCIe 5.0 x16, per direction
+
+
+def stack_flops(layers, kv_len=None):
+    tot = 0
+    for l in layers:
+        T, H, F, B, S = l.T, l.H, l.F, l.B, l.S
+        f = 2 * T * H * 3 * H + 2 * T * H * H + 4 * T * H * F
+        if l.mask == "causal":
+            f += 2 * B * S * S * H
+        elif l.mask == "keypad" and kv_len is not None:
+            f += sum(4 * S * int(v) * H for v in kv_len)
+        else:
+            f += 4 * B * S * S * H
+        if l.arch == "t5_dec":
+            Te = B * l.S_kv
+            f += 4 * T * H * H + 4 * Te * H * H + 4 * B * S * l.S_kv * H
+        tot += 3 * f
+    return tot
+
+
+def cpu_baseline(cfg, seconds_hint=20.0):
+    """Times the CPU checker (as it stands) on a bounded sample of the workload: one layer at the
+    workload's real widths with few tokens, forward + backward."""
+    import numpy as np
+    from oracle import layer_oracle as lo
+    from paper_2408_10013_amd import synth
+    arch = cfg["stack"][0][0]
+    B, S = 1, 128
+    d = lo.LayerDesc(arch=arch, B=B, S=S, H=cfg["H"], A=cfg["A"], F=cfg["F"], act=cfg["act"], norm=cfg["norm"],
+                     mask="causal" if cfg["mask"] == "causal" else "none", has_bias=cfg["has_bias"], eps=cfg["eps"])
+    shapes = lo.weight_shapes(d)
+    case = synth.make_case(shapes, d.T, d.H, synth.BASE_SEED + 99, "bf16")
+    t0 = time.perf_counter()
+    y, sv = lo.layer_fwd(d, case["w"], case["x"])
+    lo.layer_bwd(d, case["w"], sv, case["dy"])
+    dt = time.perf_counter() - t0
+    fl = lo.layer_flops(d)
+    threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    return {"value": fl / dt / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+            "sample": "1 %s layer fwd+bwd at H=%d F=%d A=%d with B=%d S=%d tokens, numpy fp64, %.1f s"
+                      % (arch, cfg["H"], cfg["F"], cfg["A"], B, S, dt)}
+
+
+def link_rate(torch, dev, nbytes=1 << 28):
+    """Measured ceiling of one pinned hipMemcpyAsync each way, GB/s."""
+    h = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
+    d = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    out = {}
+    for name, (dst, src) in {"d2h": (h, d), "h2d": (d, h)}.items():
+        dst.copy_(src, non_blocking=True)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        dst.copy_(src, non_blocking=True)
+        e1.record()
+        torch.cuda.synchronize()
+        out[name] = nbytes / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del h, d
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="gpt_8192")
+    ap.add_argument("--micro-batch", type=int, default=0, help="0 = the configuration's own")
+    ap.add_argument("--layers", type=int, default=0, help="0 = the configuration's own")
+    ap.add_argument("--modes", default="off,all,budget")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (one process, one MI355X, no collectives); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2408_10013_amd import binding as sb
+    from paper_2408_10013_amd import runner, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = torch.device("cuda:0")
+    cfg = synth.CONFIGS[args.workload]
+    B = args.micro_batch or cfg["B"]
+    layers = runner.layers_from_config(cfg, B=B, n_layers=args.layers or None)
+    L = len(layers)
+    dtype = cfg["dtype"]
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+
+    # seeded synthetic weights and inputs, generated on the device
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(synth.BASE_SEED + cfg["index"])
+    for l in layers:
+        w = {}
+        for name, shp in l.shapes.items():
+            if name.startswith("w_"):
+                w[name] = (torch.randn(shp, generator=gen, device=dev, dtype=torch.float32) * 0.02).to(tdt)
+            elif name.endswith("_g"):
+                w[name] = torch.ones(shp, device=dev, dtype=tdt)
+            else:
+                w[name] = torch.zeros(shp, device=dev, dtype=tdt)
+        l.set_weights(w)
+    first_dec = next((l for l in layers if l.arch != "t5_enc"), layers[0])
+    x = torch.randn(first_dec.T, first_dec.H, generator=gen, device=dev, dtype=torch.float32).to(tdt)
+    dy = torch.randn(first_dec.T, first_dec.H, generator=gen, device=dev, dtype=torch.float32).to(tdt)
+    enc_x = None
+    if layers[0].arch == "t5_enc":
+        enc_x = torch.randn(layers[0].T, layers[0].H, generator=gen, device=dev, dtype=torch.float32).to(tdt)
+    kv_len = None
+    if cfg.get("kv_len_range"):
+        lo_, hi_ = cfg["kv_len_range"]
+        kv_len = torch.from_numpy(np.random.default_rng(synth.BASE_SEED).integers(lo_, hi_ + 1, size=B).astype(np.int32)).to(dev)
+
+    per_layer = [runner.saved_bytes_per_layer(l) for l in layers]
+    full = sum(per_layer) + max(per_layer) + (64 << 20)   # every layer resident, plus slack
+    link = link_rate(torch, dev)
+    flops = stack_flops(layers, kv_len.cpu().numpy() if kv_len is not None else None)
+    setup = {}
+
+    def run_mode(name, budget, arena_bytes, pool_bytes, profile=False):
+        """One context per mode: the arena size is what bounds the activation memory of that mode."""
+        t0 = time.perf_counter()
+        st = runner.Stack(layers, arena_bytes, pool_bytes, "cuda:0", keep_last=1, min_offload_elems=1 << 20,
+                          budget_bytes=budget, measure_waits=1)
+        st.register_weights()
+        setup[name] = time.perf_counter() - t0
+
+        def step():
+            y = st.forward(x, enc_x=enc_x, kv_len=kv_len)
+            st.backward(dy)
+            sb.ssdt_arena_free(st.ctx, y, st.stream)
+
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
+        sb.ssdt_sync_io(st.ctx)
+        if profile:
+            sb.ssdt_profile(st.ctx, True)
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / args.steps
+        prof = None
+        if profile:
+            prof = sb.ssdt_profile_read(st.ctx)
+            sb.ssdt_profile(st.ctx, False)
+        s = st.stats()
+        st.close()
+        del st
+        torch.cuda.empty_cache()
+        return dict(ms_per_step=dt * 1e3, tflops=flops / dt / 1e12, arena_bytes=arena_bytes,
+                    bytes_offloaded=s["bytes_offloaded"], bytes_kept=s["bytes_kept"], bytes_loaded=s["bytes_loaded"],
+                    forwarded=s["forwarded"], loads=s["loads"], arena_peak_bytes=s["arena_peak_in_use"],
+                    exposed_load_wait_ms=s["exposed_load_wait_ns"] / 1e6,
+                    exposed_store_wait_ms=s["exposed_store_wait_ns"] / 1e6,
+                    link_GBps=(s["bytes_offloaded"] + s["bytes_loaded"]) / dt / 1e9), prof
+
+    modes = {}
+    want = args.modes.split(",")
+    prof = None
+    modes["off"], prof = run_mode("off", 0, full, 0, profile=("budget" not in want))
+    if "all" in want:
+        # three layers' worth of arena: the layer computing, the one being stored / loaded, and slack
+        modes["all"], _ = run_mode("all", -1, 3 * max(per_layer) + (64 << 20), runner.pool_bytes_needed(layers))
+    if "budget" in want:
+        # offload amount the link can drain while the forward runs (Sec. 3.1: the amount is set from the
+        # amount of computation, the activation size, the GPU throughput and the I/O bandwidth); the
+        # arena shrinks by what is expected to have left the device by the end of the forward pass
+        t_fwd = modes["off"]["ms_per_step"] * 1e-3 / 3.0
+        budget = int(min(0.85 * link["d2h"] * 1e9 * t_fwd, sum(per_layer[:-1])))
+        arena = full - int(0.8 * budget)
+        modes["budget"], prof = run_mode("budget", budget, arena, budget + (256 << 20), profile=True)
+        modes["budget"]["budget_bytes"] = budget
+    head = modes.get("budget") or modes["off"]
+    for k, m in modes.items():
+        m["exposed_io_pct"] = max(0.0, (m["ms_per_step"] - modes["off"]["ms_per_step"]) / m["ms_per_step"] * 100.0)
+        m["arena_peak_vs_off"] = m["arena_peak_bytes"] / max(1, modes["off"]["arena_peak_bytes"])
+
+    roof = None
+    if prof:
+        dom = max((p for p in prof if p["flops"] > 0), key=lambda p: p["ms"], default=None)
+        if dom:
+            ach = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
+            roof = {"kernel": dom["name"], "bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS,
+                    "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                    "launches": dom["launches"], "avg_launch_ms": dom["ms"] / dom["launches"]}
+    cpu = None if args.no_cpu_baseline else cpu_baseline(cfg)
+    out = {
+        "metric": "layer fwd+bwd TFLOP/s (whole stack, offload on with adaptive amount)",
+        "value": head["tflops"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": dtype, "data": "synthetic",
+        "config": {"workload": "%s: %s x%d, H=%d A=%d F=%d S=%d micro-batch %d" % (
+            args.workload, "+".join(a for a, _ in cfg["stack"]), L, cfg["H"], cfg["A"], cfg["F"], layers[-1].S, B)},
+        "mfma_peak_frac": head["tflops"] / MFMA_BF16_PEAK_TFLOPS,
+        "exposed_io_pct": head.get("exposed_io_pct"),
+        "activation_peak_vs_no_offload": head.get("arena_peak_vs_off"),
+        "offload_GBps": modes["all"]["link_GBps"] if "all" in modes else head["link_GBps"],
+        "offload_link_frac": (modes["all"]["link_GBps"] if "all" in modes else head["link_GBps"]) / (2 * HOST_LINK_PEAK_GBPS),
+        "link_measured_GBps": link, "modes": modes, "kernels": prof, "roofline": roof, "cpu_baseline": cpu,
+        "setup_s": setup,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -200,6 +200,21 @@ ssdt_status ssdt_sim_complete(ssdt_ctx *ctx, int32_t direction, int32_t n, int32
 /* Blocks the host until the store and load streams are idle. */
 ssdt_status ssdt_sync_io(ssdt_ctx *ctx);
 
+/* ---- kernel timing ------------------------------------------------------------------------ */
+
+/* Optional per-kernel-class timing: while enabled, every kernel launch of the layer entry points is
+ * bracketed with HIP events on its launch stream.  ssdt_profile_read folds the finished measurements
+ * into per-class totals (call it after synchronising the stream) and copies up to `cap` classes that
+ * have launches; `flops` / `bytes` are the algorithmic work the launches were given (2 M N K for a
+ * matrix product; the causal half for masked attention; bytes read + written for the others). */
+typedef struct ssdt_kernel_time {
+  char name[48];
+  uint64_t launches;
+  double ms, flops, bytes;
+} ssdt_kernel_time;
+ssdt_status ssdt_profile(ssdt_ctx *ctx, int32_t enable);  /* enabling also clears the totals */
+ssdt_status ssdt_profile_read(ssdt_ctx *ctx, ssdt_kernel_time *out, uint32_t cap, uint32_t *n);
+
 /* ---- the layer -------------------------------------------------------------------------- */
 
 enum { SSDT_ARCH_GPT_PRELN = 0, SSDT_ARCH_BERT_POSTLN = 1, SSDT_ARCH_T5_ENC = 2, SSDT_ARCH_T5_DEC = 3 };

@@ -64,6 +64,11 @@ class ssdt_record(C.Structure):
                 ("pool_offset", C.c_int64), ("device_ptr", C.c_void_p)]
 
 
+class ssdt_kernel_time(C.Structure):
+    _fields_ = [("name", C.c_char * 48), ("launches", C.c_uint64), ("ms", C.c_double), ("flops", C.c_double),
+                ("bytes", C.c_double)]
+
+
 class ssdt_layer_desc(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("arch", "dtype", "act", "norm", "mask", "has_bias", "B", "S", "S_kv", "H",
                                          "A", "F")] + [("eps", C.c_float), ("softmax_scale", C.c_float)]
@@ -107,6 +112,8 @@ _PROTOS = {
     "ssdt_pool_read": (C.c_int32, [C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t]),
     "ssdt_sim_complete": (C.c_int32, [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_int32)]),
     "ssdt_sync_io": (C.c_int32, [C.c_void_p]),
+    "ssdt_profile": (C.c_int32, [C.c_void_p, C.c_int32]),
+    "ssdt_profile_read": (C.c_int32, [C.c_void_p, C.POINTER(ssdt_kernel_time), C.c_uint32, C.POINTER(C.c_uint32)]),
     "ssdt_layer_workspace": (C.c_int32, [C.POINTER(ssdt_layer_desc), C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]),
     "ssdt_layer_fwd": (C.c_int32, [C.c_void_p, C.POINTER(ssdt_layer_desc), C.POINTER(ssdt_layer_weights), C.c_int32,
                                    C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_void_p),
@@ -251,6 +258,18 @@ def ssdt_sim_complete(ctx, direction, n) -> int:
 
 def ssdt_sync_io(ctx):
     _check(ctx, lib().ssdt_sync_io(ctx), "ssdt_sync_io")
+
+
+def ssdt_profile(ctx, enable: bool):
+    _check(ctx, lib().ssdt_profile(ctx, int(bool(enable))), "ssdt_profile")
+
+
+def ssdt_profile_read(ctx) -> list:
+    buf = (ssdt_kernel_time * 16)()
+    n = C.c_uint32()
+    _check(ctx, lib().ssdt_profile_read(ctx, buf, 16, C.byref(n)), "ssdt_profile_read")
+    return [dict(name=buf[i].name.decode(), launches=int(buf[i].launches), ms=buf[i].ms, flops=buf[i].flops,
+                 bytes=buf[i].bytes) for i in range(n.value)]
 
 
 def make_desc(arch="gpt_preln", dtype="f32", act="gelu", norm="layernorm", mask="causal", has_bias=True, B=1, S=1,

@@ -13,6 +13,7 @@
 // transposing LDS read (ds_read_b64_tr_b16), so no transposed copies are made.
 #include "dev.h"
 #include "kernels.h"
+#include "prof.h"
 
 namespace ssdt {
 namespace k {
@@ -190,6 +191,10 @@ static bool fa_supported(const Attn &a) {
   return true;
 }
 
+static double fa_flops(const Attn &a) {
+  return 4.0 * a.B * a.A * (double)a.Sq * a.Sk * a.d * (a.mask == SSDT_MASK_CAUSAL ? 0.5 : 1.0);
+}
+
 static FaP to_fa(const Attn &a) {
   FaP p;
   p.B = a.B; p.A = a.A; p.Sq = a.Sq; p.Sk = a.Sk; p.mask = a.mask; p.scale = a.scale; p.kv_len = a.kv_len;
@@ -204,6 +209,7 @@ hipError_t attn_fwd_mfma_bf16(const Attn &a, hipStream_t s) {
   if (!fa_supported(a) || ((uintptr_t)a.o & 7) || a.ldo % 4) return hipErrorNotSupported;
   if (a.mask == SSDT_MASK_CAUSAL && a.Sq != a.Sk) return hipErrorNotSupported;
   FaP p = to_fa(a);
+  prof::Scope ps(prof::ATTN_FWD, fa_flops(a), 0, s);
   dim3 grid(a.Sq / 128, a.A, a.B);
   if (a.d == 128) hipLaunchKernelGGL(fa_fwd_k<128>, grid, dim3(256), 0, s, p);
   else hipLaunchKernelGGL(fa_fwd_k<64>, grid, dim3(256), 0, s, p);
@@ -410,6 +416,7 @@ hipError_t attn_bwd_mfma_bf16(const Attn &a, hipStream_t s) {
   if (!al16(a.dout) || a.lddo % 8 || !al8(a.dq) || !al8(a.dk) || !al8(a.dv) || a.lddq % 4 || a.lddk % 4 || a.lddv % 4 ||
       !a.delta || !a.lse || !a.o)
     return hipErrorNotSupported;
+  prof::Scope ps(prof::ATTN_BWD, 2 * fa_flops(a), 0, s);
   hipError_t e = attn_delta(a, s);
   if (e != hipSuccess) return e;
   FaP p = to_fa(a);

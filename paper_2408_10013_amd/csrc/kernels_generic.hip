@@ -12,6 +12,7 @@
 // Sec. 2.1 names (attention block, MLP block, norms, residuals).
 #include "dev.h"
 #include "kernels.h"
+#include "prof.h"
 
 namespace ssdt {
 namespace k {
@@ -111,6 +112,7 @@ hipError_t gemm_generic(const Gemm &g, hipStream_t s) {
   GemmP p{g.M, g.N, g.K, g.A, g.B, g.C, g.C2, g.bias, g.resid, g.aux, g.lda, g.ldb, g.ldc, g.ldr,
           g.transA, g.transB, g.epi, g.act};
   dim3 grid((g.N + 63) / 64, (g.M + 63) / 64);
+  prof::Scope ps(prof::GEMM_GENERIC, 2.0 * g.M * g.N * g.K, 0, s);
   if (g.dtype == SSDT_F32) hipLaunchKernelGGL(gemm_generic_k<float>, grid, dim3(256), 0, s, p);
   else hipLaunchKernelGGL(gemm_generic_k<bf16>, grid, dim3(256), 0, s, p);
   SSDT_LAUNCH_CHECK();
@@ -162,6 +164,7 @@ __global__ __launch_bounds__(256) void norm_fwd_k(const T *x, const T *gamma, co
 hipError_t norm_fwd(const void *x, const void *gamma, const void *beta, void *y, float *mean, float *rstd, int rows,
                     int H, float eps, int kind, int dtype, hipStream_t s) {
   dim3 grid((rows + 3) / 4);
+  prof::Scope ps(prof::NORM_FWD, 0, 2.0 * rows * H * (dtype == SSDT_F32 ? 4 : 2), s);
   if (dtype == SSDT_F32)
     hipLaunchKernelGGL(norm_fwd_k<float>, grid, dim3(256), 0, s, (const float *)x, (const float *)gamma,
                        (const float *)beta, (float *)y, mean, rstd, rows, H, eps, kind);
@@ -264,6 +267,7 @@ static hipError_t colreduce(const T *a, long lda, const T *x, const float *mean,
   int chunks = colreduce_chunks(rows);
   int rpc = (rows + chunks - 1) / chunks;
   dim3 grid((cols + 127) / 128, chunks);
+  prof::Scope ps(prof::COLREDUCE, 0, (norm ? 2.0 : 1.0) * rows * cols * sizeof(T), s);
   if (norm) hipLaunchKernelGGL((colreduce1_k<T, true>), grid, dim3(256), 0, s, a, lda, x, mean, rstd, kind, partial, rows, cols, rpc);
   else hipLaunchKernelGGL((colreduce1_k<T, false>), grid, dim3(256), 0, s, a, lda, x, mean, rstd, kind, partial, rows, cols, rpc);
   SSDT_LAUNCH_CHECK();
@@ -276,12 +280,15 @@ hipError_t norm_bwd(const void *dy, const void *x, const float *mean, const floa
                     const void *resid, void *dx, void *dgamma, void *dbeta, float *partial, int rows, int H, int kind,
                     int dtype, hipStream_t s) {
   dim3 grid((rows + 3) / 4);
-  if (dtype == SSDT_F32)
-    hipLaunchKernelGGL(norm_bwd_dx_k<float>, grid, dim3(256), 0, s, (const float *)dy, (const float *)x, mean, rstd,
-                       (const float *)gamma, (const float *)resid, (float *)dx, rows, H, kind);
-  else
-    hipLaunchKernelGGL(norm_bwd_dx_k<bf16>, grid, dim3(256), 0, s, (const bf16 *)dy, (const bf16 *)x, mean, rstd,
-                       (const bf16 *)gamma, (const bf16 *)resid, (bf16 *)dx, rows, H, kind);
+  {
+    prof::Scope ps(prof::NORM_BWD, 0, (resid ? 4.0 : 3.0) * rows * H * (dtype == SSDT_F32 ? 4 : 2), s);
+    if (dtype == SSDT_F32)
+      hipLaunchKernelGGL(norm_bwd_dx_k<float>, grid, dim3(256), 0, s, (const float *)dy, (const float *)x, mean, rstd,
+                         (const float *)gamma, (const float *)resid, (float *)dx, rows, H, kind);
+    else
+      hipLaunchKernelGGL(norm_bwd_dx_k<bf16>, grid, dim3(256), 0, s, (const bf16 *)dy, (const bf16 *)x, mean, rstd,
+                         (const bf16 *)gamma, (const bf16 *)resid, (bf16 *)dx, rows, H, kind);
+  }
   SSDT_LAUNCH_CHECK();
   if (dtype == SSDT_F32)
     return colreduce<float>((const float *)dy, H, (const float *)x, mean, rstd, kind, (float *)dgamma, (float *)dbeta,
@@ -501,7 +508,12 @@ hipError_t attn_fwd(const Attn &a, hipStream_t s) {
   return attn_fwd_generic(a, s);
 }
 
+static double attn_flops(const Attn &a) {
+  return 4.0 * a.B * a.A * (double)a.Sq * a.Sk * a.d * (a.mask == SSDT_MASK_CAUSAL ? 0.5 : 1.0);
+}
+
 hipError_t attn_fwd_generic(const Attn &a, hipStream_t s) {
+  prof::Scope ps(prof::ATTN_FWD, attn_flops(a), 0, s);
   AttnP p = to_p(a);
   dim3 grid((a.Sq + 3) / 4, a.A, a.B);
   if (a.dtype == SSDT_F32) hipLaunchKernelGGL(attn_fwd_generic_k<float>, grid, dim3(256), 0, s, p);
@@ -530,6 +542,7 @@ hipError_t attn_delta(const Attn &a, hipStream_t s) {
 }
 
 hipError_t attn_bwd_generic(const Attn &a, hipStream_t s) {
+  prof::Scope ps(prof::ATTN_BWD, 2 * attn_flops(a), 0, s);
   AttnP p = to_p(a);
   dim3 gq((a.Sq + 3) / 4, a.A, a.B), gk((a.Sk + 3) / 4, a.A, a.B);
   if (a.dtype == SSDT_F32) {
@@ -562,6 +575,7 @@ __global__ __launch_bounds__(256) void transpose_k(const U *in, long ldi, U *out
 
 hipError_t transpose(const void *in, long ldi, void *out, long ldo, int rows, int cols, int dtype, hipStream_t s) {
   dim3 grid((cols + 63) / 64, (rows + 63) / 64);
+  prof::Scope ps(prof::TRANSPOSE, 0, 2.0 * rows * cols * (dtype == SSDT_F32 ? 4 : 2), s);
   if (dtype == SSDT_F32)
     hipLaunchKernelGGL(transpose_k<uint32_t>, grid, dim3(256), 0, s, (const uint32_t *)in, ldi, (uint32_t *)out, ldo, rows, cols);
   else
@@ -581,6 +595,7 @@ hipError_t add_inplace(void *y, const void *x, size_t n, int dtype, hipStream_t 
   size_t blocks = (n + 255) / 256;
   if (blocks > 65536) blocks = 65536;
   if (blocks == 0) return hipSuccess;
+  prof::Scope ps(prof::ADD, 0, 3.0 * n * (dtype == SSDT_F32 ? 4 : 2), s);
   if (dtype == SSDT_F32) hipLaunchKernelGGL(add_inplace_k<float>, dim3((unsigned)blocks), dim3(256), 0, s, (float *)y, (const float *)x, n);
   else hipLaunchKernelGGL(add_inplace_k<bf16>, dim3((unsigned)blocks), dim3(256), 0, s, (bf16 *)y, (const bf16 *)x, n);
   SSDT_LAUNCH_CHECK();

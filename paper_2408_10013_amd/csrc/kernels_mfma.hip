@@ -1,26 +1,42 @@
 // bf16 GEMM on the CDNA4 matrix cores (v_mfma_f32_32x32x16_bf16), fp32 accumulation.
 //
-// The kernel computes C[M,N] = A[M,K] . Bt[N,K]^T with both operands contiguous along K
-// ("NT"), which is the form the MFMA operand registers want (8 consecutive K per lane).
-// Other transpositions are brought to this form by a transpose into caller scratch.
+// Both kernels compute C[M,N] = A[M,K] . Bt[N,K]^T with the two operands contiguous along K
+// ("NT"), the form the MFMA operand registers want (8 consecutive K per lane).  Other
+// transpositions are brought to this form by a transpose into caller scratch.
 //
-// Work decomposition: one workgroup of 4 wavefronts per BMxBN tile of C, each wavefront
-// owning a (BM/2)x(BN/2) quadrant as a grid of 32x32 MFMA blocks; K is walked in steps of 64
-// through a double-buffered LDS tile (rows padded by 16 bytes so that the 128-bit operand
-// reads of 16 consecutive lanes fall on distinct banks).  Global loads of step k+1 are issued
-// before the MFMAs of step k and written to the other LDS buffer after them, so one barrier
-// per step suffices.  The MFMA is issued with the Bt fragment as its first operand, which
-// leaves every lane with 4 consecutive columns of one row of C: epilogue traffic is 8-byte.
-// Workgroup ids are remapped so that the ids one XCD receives (id mod 8) cover a compact
-// block of tiles, and tiles are visited in groups of rows for L2 reuse.
+// gemm_nt256_k -- the workhorse, one workgroup of 8 wavefronts per 256x256 tile of C, each
+//   wavefront owning 128x64 as 4x2 MFMA blocks (128 accumulator registers, two wavefronts per
+//   SIMD so that one's LDS reads hide behind the other's MFMAs).  K is walked in steps of 64
+//   through two 64 KiB LDS stages filled by direct global-to-LDS loads (no staging registers,
+//   no LDS store instructions): a row of a stage is one whole 128-byte cache line, so the
+//   L2-to-L1 path moves no byte twice (with 32-wide steps every line was fetched twice and that
+//   path, about 50 B/clk per compute unit, became the bound).  The 16-byte chunk c of row r is
+//   kept at slot c ^ ((r >> 1) & 7), which makes the 128-bit operand reads of 16 consecutive
+//   rows fall on distinct banks without padding (the loader applies the permutation on the
+//   global side, since a direct load writes LDS linearly by lane).  Waiting is explicit: one
+//   `s_waitcnt vmcnt(0)` and one `s_barrier` per step, then the next step's loads are issued
+//   and run under this step's 32 MFMAs per wavefront.  LDS operand reads are issued through
+//   inline assembly, one 16-wide K sub-step ahead of the MFMAs that consume them, so that the
+//   compiler does not serialise them against the in-flight loads.
+// gemm_nt128_k -- 128x128 tiles, 4 wavefronts, register-staged double-buffered LDS; for
+//   problems too small to fill 256 compute units with 256x256 tiles.
+//
+// The MFMA is issued with the Bt fragment as its first operand, which leaves every lane with 4
+// consecutive columns of one row of C: epilogue traffic (bias, residual, activation input,
+// output) is 8 bytes per access.  Workgroup ids are remapped so that the ids one XCD receives
+// (id mod 8) cover a compact block of tiles, and tiles are visited in groups of rows, for L2
+// reuse.
 #include "dev.h"
 #include "kernels.h"
+#include "prof.h"
 
 namespace ssdt {
 namespace k {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
+typedef int v4i_t __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) void lds_void_t;
 
 struct NtP {
   int M, N, K;
@@ -31,51 +47,204 @@ struct NtP {
   int act, tiles_m, tiles_n;
 };
 
-constexpr int kBK = 64;
-constexpr int kLDK = kBK + 8;  // padded LDS row, in elements
-
 __device__ __forceinline__ void unpack4(uint2 v, float *f) {
   f[0] = bf2f((uint16_t)(v.x & 0xffff)); f[1] = bf2f((uint16_t)(v.x >> 16));
   f[2] = bf2f((uint16_t)(v.y & 0xffff)); f[3] = bf2f((uint16_t)(v.y >> 16));
 }
 __device__ __forceinline__ uint2 pack4(const float *f) { return make_uint2(pack_bf2(f[0], f[1]), pack_bf2(f[2], f[3])); }
 
-template <int BM, int BN, int EPI>
-__global__ __launch_bounds__(256) void gemm_nt_k(NtP p) {
-  constexpr int WTM = BM / 2, WTN = BN / 2, TM = WTM / 32, TN = WTN / 32;
-  constexpr int CHA = BM * kBK / 8 / 256, CHB = BN * kBK / 8 / 256;
-  extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
-  constexpr int STAGE = (BM + BN) * kLDK;  // elements per LDS buffer: A tile then B tile
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave >> 1, wn = wave & 1;
-  // workgroup id -> tile: compact per XCD, then grouped along M
-  int pid = blockIdx.x;
+// workgroup id -> tile: compact per XCD, then grouped along M
+__device__ __forceinline__ void tile_of(const NtP &p, int pid, int *tile_m, int *tile_n) {
   const int nt = p.tiles_m * p.tiles_n;
   if ((nt & 7) == 0) pid = (pid & 7) * (nt >> 3) + (pid >> 3);
   constexpr int GM = 8;
   const int width = GM * p.tiles_n, group = pid / width, first_m = group * GM;
   const int gsz = min(p.tiles_m - first_m, GM);
-  const int tile_m = first_m + (pid % width) % gsz, tile_n = (pid % width) / gsz;
+  *tile_m = first_m + (pid % width) % gsz;
+  *tile_n = (pid % width) / gsz;
+}
+
+// One 32x32 accumulator block: this lane holds row m and columns n + g*8 + 0..3, g = 0..3
+// (n already includes the lane's half offset).
+template <int EPI>
+__device__ __forceinline__ void epilogue_block(const NtP &p, const f32x16_t &acc, int m, int n) {
+#pragma unroll
+  for (int g = 0; g < 4; ++g) {
+    const int nn = n + g * 8;
+    float v[4] = {acc[g * 4 + 0], acc[g * 4 + 1], acc[g * 4 + 2], acc[g * 4 + 3]};
+    if (EPI != EPI_NONE && EPI != EPI_ACTBWD && p.bias) {
+      float b[4];
+      unpack4(*(const uint2 *)(p.bias + nn), b);
+#pragma unroll
+      for (int t = 0; t < 4; ++t) v[t] += b[t];
+    }
+    const long o = (long)m * p.ldc + nn;
+    if (EPI == EPI_BIAS_ACT) {
+      if (p.C) *(uint2 *)(p.C + o) = pack4(v);
+      float a[4];
+#pragma unroll
+      for (int t = 0; t < 4; ++t) a[t] = p.act == SSDT_ACT_GELU ? gelu_f(v[t]) : fmaxf(v[t], 0.f);
+      *(uint2 *)(p.C2 + o) = pack4(a);
+    } else if (EPI == EPI_BIAS_RESID) {
+      float r[4];
+      unpack4(*(const uint2 *)(p.resid + (long)m * p.ldr + nn), r);
+#pragma unroll
+      for (int t = 0; t < 4; ++t) v[t] += r[t];
+      *(uint2 *)(p.C + o) = pack4(v);
+    } else if (EPI == EPI_ACTBWD) {
+      float u[4];
+      unpack4(*(const uint2 *)(p.aux + o), u);
+#pragma unroll
+      for (int t = 0; t < 4; ++t) v[t] *= p.act == SSDT_ACT_GELU ? gelu_grad_f(u[t]) : (u[t] > 0.f ? 1.f : 0.f);
+      *(uint2 *)(p.C + o) = pack4(v);
+    } else {
+      *(uint2 *)(p.C + o) = pack4(v);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// 256x256 tile, 8 wavefronts, two 64-wide LDS stages of direct global-to-LDS loads
+// ------------------------------------------------------------------------------------------
+constexpr int kBM2 = 256, kBN2 = 256, kBK2 = 64;
+constexpr int kStage2 = (kBM2 + kBN2) * kBK2;  // elements per stage: A rows then Bt rows, 128 bytes each
+
+__device__ __forceinline__ bf16x8_t as_bf(v4i_t v) {
+  union { v4i_t a; bf16x8_t b; } u;
+  u.a = v;
+  return u.b;
+}
+#define SSDT_DSR(dst, addr, off) asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(off))
+// operands of one 16-wide K sub-step of a 128x64 wavefront tile: 4 A fragments, 2 Bt fragments
+#define SSDT_READ6(A0, A1, A2, A3, B0, B1, aaddr, baddr)                                                  \
+  {                                                                                                       \
+    SSDT_DSR(A0, aaddr, 0); SSDT_DSR(B0, baddr, 0); SSDT_DSR(A1, aaddr, 4096);                            \
+    SSDT_DSR(B1, baddr, 4096); SSDT_DSR(A2, aaddr, 8192); SSDT_DSR(A3, aaddr, 12288);                     \
+  }
+#define SSDT_WAIT6(N, A0, A1, A2, A3, B0, B1)                                                             \
+  asm volatile("s_waitcnt lgkmcnt(" #N ")" : "+v"(A0), "+v"(A1), "+v"(A2), "+v"(A3), "+v"(B0), "+v"(B1))
+#define SSDT_MFMA8(A0, A1, A2, A3, B0, B1)                                                                \
+  {                                                                                                       \
+    acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(B0), as_bf(A0), acc[0][0], 0, 0, 0);        \
+    acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(B1), as_bf(A0), acc[0][1], 0, 0, 0);        \
+    acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(B0), as_bf(A1), acc[1][0], 0, 0, 0);        \
+    acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(B1), as_bf(A1), acc[1][1], 0, 0, 0);        \
+    acc[2][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(B0), as_bf(A2), acc[2][0], 0, 0, 0);        \
+    acc[2][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(B1), as_bf(A2), acc[2][1], 0, 0, 0);        \
+    acc[3][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(B0), as_bf(A3), acc[3][0], 0, 0, 0);        \
+    acc[3][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(B1), as_bf(A3), acc[3][1], 0, 0, 0);        \
+  }
+
+template <int EPI>
+__global__ __launch_bounds__(512) void gemm_nt256_k(NtP p) {
+  extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave >> 2, wn = wave & 3;
+  int tile_m, tile_n;
+  tile_of(p, blockIdx.x, &tile_m, &tile_n);
+  const int m0 = tile_m * kBM2, n0 = tile_n * kBN2;
+
+  // loader: thread t fills LDS positions j*512 + t (16-byte units), j = 0..3, of A and of Bt:
+  // row j*64 + t/8, slot t%8, which holds global chunk (t%8) ^ ((row >> 1) & 7) of that row;
+  // 8 consecutive lanes fetch one whole 128-byte line
+  const int lrow = tid >> 3, lchunk = (tid & 7) ^ ((lrow >> 1) & 7);
+  const uint16_t *ga = p.A + (long)(m0 + lrow) * p.lda + lchunk * 8;
+  const uint16_t *gb = p.Bt + (long)(n0 + lrow) * p.ldb + lchunk * 8;
+  const long a64 = 64 * p.lda, b64 = 64 * p.ldb;
+  uint16_t *s_wave = smem + wave * 64 * 8;  // a wavefront's 64 positions are contiguous: 1 KiB per load
+#define SSDT_ISSUE(kt)                                                                                    \
+  {                                                                                                       \
+    uint16_t *sb_ = s_wave + ((kt) & 1) * kStage2;                                                        \
+    const long ko_ = (long)(kt) * kBK2;                                                                   \
+    _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                       \
+      __builtin_amdgcn_global_load_lds(ga + j * a64 + ko_, (lds_void_t *)(sb_ + j * 64 * kBK2), 16, 0, 0); \
+      __builtin_amdgcn_global_load_lds(gb + j * b64 + ko_, (lds_void_t *)(sb_ + kBM2 * kBK2 + j * 64 * kBK2), 16, 0, 0); \
+    }                                                                                                     \
+  }
+
+  f32x16_t acc[4][2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int nk = p.K / kBK2;
+  SSDT_ISSUE(0);
+
+  const int li = lane & 31, half = lane >> 5;
+  const unsigned sw = (li >> 1) & 7;
+  const unsigned lds0 = (unsigned)(uintptr_t)smem;
+  // LDS byte addresses (stage 0) of this lane's first A / Bt fragment rows for the four sub-steps
+  const unsigned arow = lds0 + (wm * 128 + li) * 128, brow = lds0 + (kBM2 + wn * 64 + li) * 128;
+  const unsigned oa0 = arow + ((0 + half) ^ sw) * 16, oa1 = arow + ((2 + half) ^ sw) * 16;
+  const unsigned oa2 = arow + ((4 + half) ^ sw) * 16, oa3 = arow + ((6 + half) ^ sw) * 16;
+  const unsigned ob0 = brow + ((0 + half) ^ sw) * 16, ob1 = brow + ((2 + half) ^ sw) * 16;
+  const unsigned ob2 = brow + ((4 + half) ^ sw) * 16, ob3 = brow + ((6 + half) ^ sw) * 16;
+  v4i_t pa0, pa1, pa2, pa3, pb0, pb1, qa0, qa1, qa2, qa3, qb0, qb1;
+
+  for (int kt = 0; kt < nk; ++kt) {
+    __builtin_amdgcn_s_waitcnt(0xF70);  // vmcnt(0): this wavefront's part of stage kt has landed
+    __builtin_amdgcn_s_barrier();       // so has everyone's; and everyone is done reading stage kt-1
+    if (kt + 1 < nk) SSDT_ISSUE(kt + 1);
+    const unsigned so = (kt & 1) * kStage2 * 2;
+    SSDT_READ6(pa0, pa1, pa2, pa3, pb0, pb1, oa0 + so, ob0 + so);
+    SSDT_READ6(qa0, qa1, qa2, qa3, qb0, qb1, oa1 + so, ob1 + so);
+    SSDT_WAIT6(6, pa0, pa1, pa2, pa3, pb0, pb1);
+    SSDT_MFMA8(pa0, pa1, pa2, pa3, pb0, pb1);
+    SSDT_READ6(pa0, pa1, pa2, pa3, pb0, pb1, oa2 + so, ob2 + so);
+    SSDT_WAIT6(6, qa0, qa1, qa2, qa3, qb0, qb1);
+    SSDT_MFMA8(qa0, qa1, qa2, qa3, qb0, qb1);
+    SSDT_READ6(qa0, qa1, qa2, qa3, qb0, qb1, oa3 + so, ob3 + so);
+    SSDT_WAIT6(6, pa0, pa1, pa2, pa3, pb0, pb1);
+    SSDT_MFMA8(pa0, pa1, pa2, pa3, pb0, pb1);
+    SSDT_WAIT6(0, qa0, qa1, qa2, qa3, qb0, qb1);
+    SSDT_MFMA8(qa0, qa1, qa2, qa3, qb0, qb1);
+  }
+#undef SSDT_ISSUE
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+      epilogue_block<EPI>(p, acc[i][j], m0 + wm * 128 + i * 32 + li, n0 + wn * 64 + j * 32 + half * 4);
+}
+
+// ------------------------------------------------------------------------------------------
+// 128x128 tile, 4 wavefronts, register-staged double-buffered LDS (rows padded by 16 bytes)
+// ------------------------------------------------------------------------------------------
+constexpr int kBK = 64;
+constexpr int kLDK = kBK + 8;
+
+template <int EPI>
+__global__ __launch_bounds__(256) void gemm_nt128_k(NtP p) {
+  constexpr int BM = 128, BN = 128, WTM = 64, WTN = 64, TM = 2, TN = 2;
+  constexpr int STAGE = (BM + BN) * kLDK;
+  extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave >> 1, wn = wave & 1;
+  int tile_m, tile_n;
+  tile_of(p, blockIdx.x, &tile_m, &tile_n);
   const int m0 = tile_m * BM, n0 = tile_n * BN;
-
-  const uint16_t *Ag = p.A + (long)m0 * p.lda, *Bg = p.Bt + (long)n0 * p.ldb;
-  // each thread moves CHA + CHB 16-byte chunks per K step: chunk c covers row c/8, k-offset (c%8)*8
+  // each thread moves 4 + 4 16-byte chunks per K step: rows ld_row + 32 i, k-offset ld_kc
   const int ld_row = tid >> 3, ld_kc = (tid & 7) * 8;
-  const uint16_t *ag = Ag + (long)ld_row * p.lda + ld_kc, *bg = Bg + (long)ld_row * p.ldb + ld_kc;
-  const long a_step = 32 * p.lda, b_step = 32 * p.ldb;  // 256 threads cover 32 rows per chunk index
+  const uint16_t *ag = p.A + (long)(m0 + ld_row) * p.lda + ld_kc, *bg = p.Bt + (long)(n0 + ld_row) * p.ldb + ld_kc;
+  const long a_step = 32 * p.lda, b_step = 32 * p.ldb;
   uint16_t *s_st = smem + ld_row * kLDK + ld_kc;
-  uint4 ra[CHA], rb[CHB];
-#define SSDT_GLOAD(kt)                                                                   \
-  {                                                                                      \
-    _Pragma("unroll") for (int i = 0; i < CHA; ++i) ra[i] = *(const uint4 *)(ag + i * a_step + (kt) * kBK); \
-    _Pragma("unroll") for (int i = 0; i < CHB; ++i) rb[i] = *(const uint4 *)(bg + i * b_step + (kt) * kBK); \
+  uint4 ra0, ra1, ra2, ra3, rb0, rb1, rb2, rb3;
+#define SSDT_GLOAD(kt)                                                                                 \
+  {                                                                                                    \
+    const long ko_ = (long)(kt) * kBK;                                                                 \
+    ra0 = *(const uint4 *)(ag + ko_); ra1 = *(const uint4 *)(ag + a_step + ko_);                       \
+    ra2 = *(const uint4 *)(ag + 2 * a_step + ko_); ra3 = *(const uint4 *)(ag + 3 * a_step + ko_);      \
+    rb0 = *(const uint4 *)(bg + ko_); rb1 = *(const uint4 *)(bg + b_step + ko_);                       \
+    rb2 = *(const uint4 *)(bg + 2 * b_step + ko_); rb3 = *(const uint4 *)(bg + 3 * b_step + ko_);      \
   }
-#define SSDT_SSTORE(buf)                                                                 \
-  {                                                                                      \
-    _Pragma("unroll") for (int i = 0; i < CHA; ++i) *(uint4 *)(s_st + (buf) * STAGE + i * 32 * kLDK) = ra[i]; \
-    _Pragma("unroll") for (int i = 0; i < CHB; ++i) *(uint4 *)(s_st + (buf) * STAGE + BM * kLDK + i * 32 * kLDK) = rb[i]; \
+#define SSDT_SSTORE(buf)                                                                               \
+  {                                                                                                    \
+    uint16_t *d_ = s_st + (buf) * STAGE;                                                               \
+    *(uint4 *)(d_) = ra0; *(uint4 *)(d_ + 32 * kLDK) = ra1; *(uint4 *)(d_ + 64 * kLDK) = ra2; *(uint4 *)(d_ + 96 * kLDK) = ra3; \
+    d_ += BM * kLDK;                                                                                   \
+    *(uint4 *)(d_) = rb0; *(uint4 *)(d_ + 32 * kLDK) = rb1; *(uint4 *)(d_ + 64 * kLDK) = rb2; *(uint4 *)(d_ + 96 * kLDK) = rb3; \
   }
-
   f32x16_t acc[TM][TN];
 #pragma unroll
   for (int i = 0; i < TM; ++i)
@@ -83,22 +252,20 @@ __global__ __launch_bounds__(256) void gemm_nt_k(NtP p) {
     for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
   const int frag_off = (lane & 31) * kLDK + (lane >> 5) * 8;
   const uint16_t *a_frag = smem + (wm * WTM) * kLDK + frag_off;
   const uint16_t *b_frag = smem + BM * kLDK + (wn * WTN) * kLDK + frag_off;
-#define SSDT_COMPUTE(buf)                                                                \
-  {                                                                                      \
-    _Pragma("unroll") for (int kk = 0; kk < kBK / 16; ++kk) {                            \
-      bf16x8_t af[TM], bfr[TN];                                                          \
+#define SSDT_COMPUTE(buf)                                                                              \
+  {                                                                                                    \
+    _Pragma("unroll") for (int kk = 0; kk < kBK / 16; ++kk) {                                          \
+      bf16x8_t af[TM], bfr[TN];                                                                        \
       _Pragma("unroll") for (int i = 0; i < TM; ++i) af[i] = *(const bf16x8_t *)(a_frag + (buf) * STAGE + i * 32 * kLDK + kk * 16); \
       _Pragma("unroll") for (int j = 0; j < TN; ++j) bfr[j] = *(const bf16x8_t *)(b_frag + (buf) * STAGE + j * 32 * kLDK + kk * 16); \
-      _Pragma("unroll") for (int i = 0; i < TM; ++i)                                     \
-        _Pragma("unroll") for (int j = 0; j < TN; ++j)                                   \
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0); \
-    }                                                                                    \
+      _Pragma("unroll") for (int i = 0; i < TM; ++i)                                                   \
+        _Pragma("unroll") for (int j = 0; j < TN; ++j)                                                 \
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);      \
+    }                                                                                                  \
   }
-
   const int nk = p.K / kBK;
   SSDT_GLOAD(0);
   SSDT_SSTORE(0);
@@ -115,72 +282,54 @@ __global__ __launch_bounds__(256) void gemm_nt_k(NtP p) {
 #undef SSDT_GLOAD
 #undef SSDT_SSTORE
 #undef SSDT_COMPUTE
-
-  // epilogue: lane holds row m = (lane & 31), columns n = g*8 + (lane >> 5)*4 + 0..3 of each block
 #pragma unroll
-  for (int i = 0; i < TM; ++i) {
-    const int m = m0 + wm * WTM + i * 32 + (lane & 31);
+  for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int n = n0 + wn * WTN + j * 32 + g * 8 + (lane >> 5) * 4;
-        float v[4] = {acc[i][j][g * 4 + 0], acc[i][j][g * 4 + 1], acc[i][j][g * 4 + 2], acc[i][j][g * 4 + 3]};
-        if (EPI != EPI_NONE && EPI != EPI_ACTBWD && p.bias) {
-          float b[4];
-          unpack4(*(const uint2 *)(p.bias + n), b);
-#pragma unroll
-          for (int t = 0; t < 4; ++t) v[t] += b[t];
-        }
-        const long o = (long)m * p.ldc + n;
-        if (EPI == EPI_BIAS_ACT) {
-          if (p.C) *(uint2 *)(p.C + o) = pack4(v);
-          float a[4];
-#pragma unroll
-          for (int t = 0; t < 4; ++t) a[t] = p.act == SSDT_ACT_GELU ? gelu_f(v[t]) : fmaxf(v[t], 0.f);
-          *(uint2 *)(p.C2 + o) = pack4(a);
-        } else if (EPI == EPI_BIAS_RESID) {
-          float r[4];
-          unpack4(*(const uint2 *)(p.resid + (long)m * p.ldr + n), r);
-#pragma unroll
-          for (int t = 0; t < 4; ++t) v[t] += r[t];
-          *(uint2 *)(p.C + o) = pack4(v);
-        } else if (EPI == EPI_ACTBWD) {
-          float u[4];
-          unpack4(*(const uint2 *)(p.aux + o), u);
-#pragma unroll
-          for (int t = 0; t < 4; ++t) v[t] *= p.act == SSDT_ACT_GELU ? gelu_grad_f(u[t]) : (u[t] > 0.f ? 1.f : 0.f);
-          *(uint2 *)(p.C + o) = pack4(v);
-        } else {
-          *(uint2 *)(p.C + o) = pack4(v);
-        }
-      }
-    }
-  }
+    for (int j = 0; j < TN; ++j)
+      epilogue_block<EPI>(p, acc[i][j], m0 + wm * WTM + i * 32 + (lane & 31), n0 + wn * WTN + j * 32 + (lane >> 5) * 4);
 }
 
-template <int BM, int BN, int EPI>
-static hipError_t launch_nt(const NtP &p, hipStream_t s) {
-  constexpr size_t smem = (size_t)2 * (BM + BN) * kLDK * 2;
+template <int EPI>
+static hipError_t launch256(const NtP &p, hipStream_t s) {
+  constexpr size_t smem = (size_t)2 * kStage2 * 2;
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void *)gemm_nt_k<BM, BN, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    hipError_t e = hipFuncSetAttribute((const void *)gemm_nt256_k<EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((gemm_nt_k<BM, BN, EPI>), dim3(p.tiles_m * p.tiles_n), dim3(256), smem, s, p);
+  prof::Scope ps(prof::GEMM_MFMA_256, 2.0 * p.M * p.N * p.K, 0, s);
+  hipLaunchKernelGGL((gemm_nt256_k<EPI>), dim3(p.tiles_m * p.tiles_n), dim3(512), smem, s, p);
   return hipGetLastError();
 }
 
-template <int BM, int BN>
-static hipError_t launch_nt_epi(int epi, const NtP &p, hipStream_t s) {
-  switch (epi) {
-    case EPI_NONE: return launch_nt<BM, BN, EPI_NONE>(p, s);
-    case EPI_BIAS: return launch_nt<BM, BN, EPI_BIAS>(p, s);
-    case EPI_BIAS_ACT: return launch_nt<BM, BN, EPI_BIAS_ACT>(p, s);
-    case EPI_BIAS_RESID: return launch_nt<BM, BN, EPI_BIAS_RESID>(p, s);
-    case EPI_ACTBWD: return launch_nt<BM, BN, EPI_ACTBWD>(p, s);
+template <int EPI>
+static hipError_t launch128(const NtP &p, hipStream_t s) {
+  constexpr size_t smem = (size_t)2 * (128 + 128) * kLDK * 2;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void *)gemm_nt128_k<EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
   }
+  prof::Scope ps(prof::GEMM_MFMA_128, 2.0 * p.M * p.N * p.K, 0, s);
+  hipLaunchKernelGGL((gemm_nt128_k<EPI>), dim3(p.tiles_m * p.tiles_n), dim3(256), smem, s, p);
+  return hipGetLastError();
+}
+
+int g_force_tile = 0;   // test hook: 0 = choose, 128 or 256
+int g_force_waves = 0;  // unused
+
+static hipError_t launch_epi(bool big, int epi, const NtP &p, hipStream_t s) {
+#define SSDT_CASE(E) case E: return big ? launch256<E>(p, s) : launch128<E>(p, s);
+  switch (epi) {
+    SSDT_CASE(EPI_NONE)
+    SSDT_CASE(EPI_BIAS)
+    SSDT_CASE(EPI_BIAS_ACT)
+    SSDT_CASE(EPI_BIAS_RESID)
+    SSDT_CASE(EPI_ACTBWD)
+  }
+#undef SSDT_CASE
   return hipErrorInvalidValue;
 }
 
@@ -196,7 +345,6 @@ size_t gemm_scratch_bytes(int M, int N, int K, bool transA, bool transB, int dty
   return b;
 }
 
-int g_force_tile = 0;  // test hook: 0 = choose, 128 or 256
 
 hipError_t gemm_mfma_bf16(const Gemm &g, hipStream_t s) {
   if (g.dtype != SSDT_BF16) return hipErrorNotSupported;
@@ -231,12 +379,10 @@ hipError_t gemm_mfma_bf16(const Gemm &g, hipStream_t s) {
   bool big = (g.M % 256 == 0) && (g.N % 256 == 0) && ((long)(g.M / 256) * (g.N / 256) >= 256);
   if (g_force_tile == 128) big = false;
   if (g_force_tile == 256 && g.M % 256 == 0 && g.N % 256 == 0) big = true;
-  if (big) {
-    p.tiles_m = g.M / 256; p.tiles_n = g.N / 256;
-    return launch_nt_epi<256, 256>(g.epi, p, s);
-  }
-  p.tiles_m = g.M / 128; p.tiles_n = g.N / 128;
-  return launch_nt_epi<128, 128>(g.epi, p, s);
+  const int t = big ? 256 : 128;
+  p.tiles_m = g.M / t;
+  p.tiles_n = g.N / t;
+  return launch_epi(big, g.epi, p, s);
 }
 
 }  // namespace k

@@ -8,6 +8,7 @@
 #include <algorithm>
 
 #include "ctx.h"
+#include "prof.h"
 
 namespace ssdt {
 
@@ -605,6 +606,32 @@ ssdt_status ssdt_sim_complete(ssdt_ctx *c, int32_t dir, int32_t n, int32_t *done
   int k = c->be->sim_complete(dir, n);
   if (k < 0) return c->fail(SSDT_E_UNSUPPORTED, "sim_complete: not the simulated backend");
   if (done) *done = k;
+  return SSDT_OK;
+}
+
+ssdt_status ssdt_profile(ssdt_ctx *c, int32_t enable) {
+  if (!c) return SSDT_E_INVAL;
+  if (c->be->is_sim()) return c->fail(SSDT_E_UNSUPPORTED, "profile: the simulated backend launches no kernels");
+  if (enable) prof::reset();
+  prof::set(enable != 0);
+  return SSDT_OK;
+}
+
+ssdt_status ssdt_profile_read(ssdt_ctx *c, ssdt_kernel_time *out, uint32_t cap, uint32_t *n) {
+  if (!c || !out || !n) return SSDT_E_INVAL;
+  if (c->be->is_sim()) return c->fail(SSDT_E_UNSUPPORTED, "profile: the simulated backend launches no kernels");
+  prof::collect();
+  uint32_t k = 0;
+  for (int cat = 0; cat < prof::NCAT && k < cap; ++cat) {
+    unsigned long long l;
+    double ms, fl, by;
+    prof::totals(cat, &l, &ms, &fl, &by);
+    if (!l) continue;
+    snprintf(out[k].name, sizeof out[k].name, "%s", prof::name(cat));
+    out[k].launches = l; out[k].ms = ms; out[k].flops = fl; out[k].bytes = by;
+    ++k;
+  }
+  *n = k;
   return SSDT_OK;
 }
 

@@ -229,3 +229,19 @@ def saved_bytes_per_layer(l: Layer) -> int:
     if l.arch == "t5_dec":
         n += (4 * T * H + 3 * l.B * l.S_kv * H) * e
     return n + 64 * 256
+
+
+def pool_bytes_needed(layers: List[Layer], keep_last: int = 1, min_offload_elems: int = 1 << 20) -> int:
+    """Pinned-pool bytes that offloading every eligible tensor of every layer but the last
+    `keep_last` takes (tensor sizes rounded to 256 bytes, one 4 KiB-rounded pack per layer)."""
+    tot = 0
+    for l in layers[:len(layers) - keep_last]:
+        e = 4 if l.dtype == "f32" else 2
+        T, H, F = l.T, l.H, l.F
+        sizes = [(T * H, e)] * (5 if l.arch != "t5_dec" else 9) + [(T * 3 * H, e)] + [(T * F, e)] * 2
+        sizes += [(l.B * l.A * l.S, 4)] * (2 if l.arch == "t5_dec" else 1) + [(T, 4)] * 6
+        if l.arch == "t5_dec":
+            sizes += [(l.B * l.S_kv * H, e), (l.B * l.S_kv * 2 * H, e)]
+        pack = sum((n * b + 255) // 256 * 256 for n, b in sizes if n >= min_offload_elems)
+        tot += (pack + 4095) // 4096 * 4096
+    return tot + (1 << 20)
