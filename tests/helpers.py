@@ -27,6 +27,13 @@ def rel_err(got: np.ndarray, ref: np.ndarray) -> float:
     return float(np.abs(got - ref).max() / denom) if denom > 0 else float(np.abs(got).max())
 
 
+def rel_l2(got: np.ndarray, ref: np.ndarray) -> float:
+    ref = np.asarray(ref, dtype=np.float64).ravel()
+    got = np.asarray(got, dtype=np.float64).ravel()
+    n = np.linalg.norm(ref)
+    return float(np.linalg.norm(got - ref) / n) if n > 0 else float(np.linalg.norm(got))
+
+
 def oracle_desc(l: runner.Layer) -> lo.LayerDesc:
     return lo.LayerDesc(arch=l.arch, B=l.B, S=l.S, S_kv=l.S_kv, H=l.H, A=l.A, F=l.F, act=l.act, norm=l.norm,
                         mask=l.mask, has_bias=l.has_bias, eps=l.eps)
@@ -74,9 +81,7 @@ def registry_expectation(layers, keep_last, min_offload_elems, budget_bytes, poo
         tr = ro.saved_trace(l.arch, l.norm, l.act, l.T, l.H, l.F, l.B, l.A, l.S, e, T_enc=l.B * l.S_kv)
         reg.scope_begin(i)
         for name, storage, sbytes, numel in tr:
-            if storage == "x" and i > 0 and layers[i - 1].arch == l.arch:
-                key = (i, "x")                       # the previous layer's output: a new storage
-            elif storage == "enc":
+            if storage == "enc":
                 key = "enc"
             else:
                 key = (i, storage)
