@@ -200,7 +200,7 @@ def main():
         # arena shrinks by what is expected to have left the device by the end of the forward pass
         t_fwd = modes["off"]["ms_per_step"] * 1e-3 / 3.0
         budget = int(min(0.85 * link["d2h"] * 1e9 * t_fwd, sum(per_layer[:-1])))
-        arena = full - int(0.8 * budget)
+        arena = modes["off"]["arena_peak_bytes"] + (256 << 20) - int(0.8 * budget)
         modes["budget"], prof = run_mode("budget", budget, arena, budget + (256 << 20), profile=True)
         modes["budget"]["budget_bytes"] = budget
     head = modes.get("budget") or modes["off"]

@@ -92,6 +92,14 @@ hipError_t transpose(const void *in, long ldi, void *out, long ldo, int rows, in
 // y += x  (elementwise, n elements)
 hipError_t add_inplace(void *y, const void *x, size_t n, int dtype, hipStream_t s);
 
+// 16-byte-vectorised bf16 row kernels; return hipErrorNotSupported when the shape / alignment does not fit
+hipError_t norm_fwd_vec(const void *x, const void *gamma, const void *beta, void *y, float *mean, float *rstd, int rows,
+                        int H, float eps, int kind, hipStream_t s);
+hipError_t norm_bwd_dx_vec(const void *dy, const void *x, const float *mean, const float *rstd, const void *gamma,
+                           const void *resid, void *dx, int rows, int H, int kind, hipStream_t s);
+hipError_t colreduce1_vec(const void *a, long lda, const void *x, const float *mean, const float *rstd, int kind,
+                          float *partial, int rows, int cols, int chunks, bool norm, hipStream_t s);
+
 // fast paths (bf16 on the matrix cores); return hipErrorNotSupported when the shape does not fit
 hipError_t gemm_mfma_bf16(const Gemm &g, hipStream_t s);
 hipError_t attn_fwd_mfma_bf16(const Attn &a, hipStream_t s);

@@ -73,6 +73,28 @@ __device__ __forceinline__ void load_tile(const uint16_t *g, long ld, int valid,
   }
 }
 
+// the same copy split in two, so that the global loads of the next tile can be in flight while the
+// current tile is consumed: tile_gload issues the loads into registers, tile_sstore writes them to LDS
+template <int D, int ROWS>
+__device__ __forceinline__ void tile_gload(const uint16_t *g, long ld, int valid, int tid, uint4 (&r)[ROWS * (D / 8) / 256]) {
+  constexpr int CPR = D / 8, N = ROWS * CPR / 256;
+#pragma unroll
+  for (int i = 0; i < N; ++i) {
+    int c = tid + i * 256, row = c / CPR, kc = c % CPR;
+    r[i] = make_uint4(0, 0, 0, 0);
+    if (row < valid) r[i] = *(const uint4 *)(g + (long)row * ld + kc * 8);
+  }
+}
+template <int D, int ROWS, int LDS_LD>
+__device__ __forceinline__ void tile_sstore(uint16_t *s, int tid, const uint4 (&r)[ROWS * (D / 8) / 256]) {
+  constexpr int CPR = D / 8, N = ROWS * CPR / 256;
+#pragma unroll
+  for (int i = 0; i < N; ++i) {
+    int c = tid + i * 256, row = c / CPR, kc = c % CPR;
+    *(uint4 *)(s + row * LDS_LD + kc * 8) = r[i];
+  }
+}
+
 // ------------------------------------------------------------------------------------------
 // forward: one workgroup = 128 queries of one (sequence, head); each wavefront 32 queries
 // ------------------------------------------------------------------------------------------
@@ -103,12 +125,21 @@ __global__ __launch_bounds__(256, 2) void fa_fwd_k(FaP p) {
     for (int r = 0; r < 16; ++r) oacc[d][r] = 0.f;
   const uint16_t *kg = p.k + (long)b * p.Sk * p.ldk + h * D, *vg = p.v + (long)b * p.Sk * p.ldv + h * D;
 
+  uint4 rk[BKV * (D / 8) / 256], rv[BKV * (D / 8) / 256];
+  if (ntiles > 0) {
+    tile_gload<D, BKV>(kg, p.ldk, p.Sk, tid, rk);
+    tile_gload<D, BKV>(vg, p.ldv, p.Sk, tid, rv);
+  }
   for (int t = 0; t < ntiles; ++t) {
     const int j0 = t * BKV;
+    __syncthreads();  // everyone is done with the previous tile
+    tile_sstore<D, BKV, LK>(sK, tid, rk);
+    tile_sstore<D, BKV, LV>(sV, tid, rv);
     __syncthreads();
-    load_tile<D, BKV, LK>(kg + (long)j0 * p.ldk, p.ldk, p.Sk - j0, sK, tid);
-    load_tile<D, BKV, LV>(vg + (long)j0 * p.ldv, p.ldv, p.Sk - j0, sV, tid);
-    __syncthreads();
+    if (t + 1 < ntiles) {  // next tile's loads fly under this tile's MFMAs
+      tile_gload<D, BKV>(kg + (long)(j0 + BKV) * p.ldk, p.ldk, p.Sk - j0 - BKV, tid, rk);
+      tile_gload<D, BKV>(vg + (long)(j0 + BKV) * p.ldv, p.ldv, p.Sk - j0 - BKV, tid, rv);
+    }
     if (p.mask == SSDT_MASK_CAUSAL && j0 > q0 + 31) continue;  // tile entirely above this wavefront's diagonal
     f32x16_t sacc[2];
 #pragma unroll
@@ -221,7 +252,7 @@ hipError_t attn_fwd_mfma_bf16(const Attn &a, hipStream_t s) {
 // loops over 64-query tiles of Q and dO.  dK[j] = scale sum_i dS_ij q_i, dV[j] = sum_i P_ij dO_i.
 // ------------------------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(256, 2) void fa_bwd_dkv_k(FaP p) {
+__global__ __launch_bounds__(256, (D == 128 ? 1 : 2)) void fa_bwd_dkv_k(FaP p) {
   constexpr int BQ = 64, LQ = D + 8, KS = D / 16, DB = D / 32;
   __shared__ __attribute__((aligned(16))) uint16_t sQ[BQ * LQ];
   __shared__ __attribute__((aligned(16))) uint16_t sdO[BQ * LQ];
@@ -250,14 +281,29 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dkv_k(FaP p) {
   const int t0 = (p.mask == SSDT_MASK_CAUSAL) ? (int)(blockIdx.x * 128) / BQ : 0;
   const bool block_live = (int)(blockIdx.x * 128) < limit;
 
-  for (int t = block_live ? t0 : nt; t < nt; ++t) {
+  const int tstart = block_live ? t0 : nt;
+  uint4 rq[BQ * (D / 8) / 256], rdo[BQ * (D / 8) / 256];
+  float rstat = 0.f;
+  if (tstart < nt) {
+    tile_gload<D, BQ>(qg + (long)tstart * BQ * p.ldq, p.ldq, BQ, tid, rq);
+    tile_gload<D, BQ>(dog + (long)tstart * BQ * p.lddo, p.lddo, BQ, tid, rdo);
+    if (tid < BQ) rstat = lse_g[tstart * BQ + tid];
+    else if (tid < 2 * BQ) rstat = delta_g[tstart * BQ + tid - BQ];
+  }
+  for (int t = tstart; t < nt; ++t) {
     const int i0 = t * BQ;
     __syncthreads();
-    load_tile<D, BQ, LQ>(qg + (long)i0 * p.ldq, p.ldq, BQ, sQ, tid);
-    load_tile<D, BQ, LQ>(dog + (long)i0 * p.lddo, p.lddo, BQ, sdO, tid);
-    if (tid < BQ) sLse[tid] = lse_g[i0 + tid];
-    else if (tid < 2 * BQ) sDelta[tid - BQ] = delta_g[i0 + tid - BQ];
+    tile_sstore<D, BQ, LQ>(sQ, tid, rq);
+    tile_sstore<D, BQ, LQ>(sdO, tid, rdo);
+    if (tid < BQ) sLse[tid] = rstat;
+    else if (tid < 2 * BQ) sDelta[tid - BQ] = rstat;
     __syncthreads();
+    if (t + 1 < nt) {
+      tile_gload<D, BQ>(qg + (long)(i0 + BQ) * p.ldq, p.ldq, BQ, tid, rq);
+      tile_gload<D, BQ>(dog + (long)(i0 + BQ) * p.lddo, p.lddo, BQ, tid, rdo);
+      if (tid < BQ) rstat = lse_g[i0 + BQ + tid];
+      else if (tid < 2 * BQ) rstat = delta_g[i0 + BQ + tid - BQ];
+    }
     if (p.mask == SSDT_MASK_CAUSAL && i0 + BQ - 1 < k0) continue;  // every query of the tile precedes this wavefront's keys
     const bool need_mask = (p.mask == SSDT_MASK_CAUSAL && i0 < k0 + 31) || (k0 + 32 > limit);
 #pragma unroll
@@ -354,12 +400,21 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dq_k(FaP p) {
     for (int r = 0; r < 16; ++r) dqacc[d][r] = 0.f;
   const uint16_t *kg = p.k + (long)b * p.Sk * p.ldk + h * D, *vg = p.v + (long)b * p.Sk * p.ldv + h * D;
 
+  uint4 rk[BKV * (D / 8) / 256], rv[BKV * (D / 8) / 256];
+  if (ntiles > 0) {
+    tile_gload<D, BKV>(kg, p.ldk, p.Sk, tid, rk);
+    tile_gload<D, BKV>(vg, p.ldv, p.Sk, tid, rv);
+  }
   for (int t = 0; t < ntiles; ++t) {
     const int j0 = t * BKV;
     __syncthreads();
-    load_tile<D, BKV, LK>(kg + (long)j0 * p.ldk, p.ldk, p.Sk - j0, sK, tid);
-    load_tile<D, BKV, LK>(vg + (long)j0 * p.ldv, p.ldv, p.Sk - j0, sV, tid);
+    tile_sstore<D, BKV, LK>(sK, tid, rk);
+    tile_sstore<D, BKV, LK>(sV, tid, rv);
     __syncthreads();
+    if (t + 1 < ntiles) {
+      tile_gload<D, BKV>(kg + (long)(j0 + BKV) * p.ldk, p.ldk, p.Sk - j0 - BKV, tid, rk);
+      tile_gload<D, BKV>(vg + (long)(j0 + BKV) * p.ldv, p.ldv, p.Sk - j0 - BKV, tid, rv);
+    }
     if (p.mask == SSDT_MASK_CAUSAL && j0 > q0 + 31) continue;
     const bool need_mask = (p.mask == SSDT_MASK_CAUSAL && j0 + BKV - 1 > q0) || (j0 + BKV > limit);
 #pragma unroll

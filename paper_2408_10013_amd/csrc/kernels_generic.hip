@@ -163,6 +163,10 @@ __global__ __launch_bounds__(256) void norm_fwd_k(const T *x, const T *gamma, co
 
 hipError_t norm_fwd(const void *x, const void *gamma, const void *beta, void *y, float *mean, float *rstd, int rows,
                     int H, float eps, int kind, int dtype, hipStream_t s) {
+  if (dtype == SSDT_BF16) {
+    hipError_t e = norm_fwd_vec(x, gamma, beta, y, mean, rstd, rows, H, eps, kind, s);
+    if (e != hipErrorNotSupported) return e;
+  }
   dim3 grid((rows + 3) / 4);
   prof::Scope ps(prof::NORM_FWD, 0, 2.0 * rows * H * (dtype == SSDT_F32 ? 4 : 2), s);
   if (dtype == SSDT_F32)
@@ -268,8 +272,12 @@ static hipError_t colreduce(const T *a, long lda, const T *x, const float *mean,
   int rpc = (rows + chunks - 1) / chunks;
   dim3 grid((cols + 127) / 128, chunks);
   prof::Scope ps(prof::COLREDUCE, 0, (norm ? 2.0 : 1.0) * rows * cols * sizeof(T), s);
-  if (norm) hipLaunchKernelGGL((colreduce1_k<T, true>), grid, dim3(256), 0, s, a, lda, x, mean, rstd, kind, partial, rows, cols, rpc);
-  else hipLaunchKernelGGL((colreduce1_k<T, false>), grid, dim3(256), 0, s, a, lda, x, mean, rstd, kind, partial, rows, cols, rpc);
+  hipError_t ev = sizeof(T) == 2 ? colreduce1_vec(a, lda, x, mean, rstd, kind, partial, rows, cols, chunks, norm, s) : hipErrorNotSupported;
+  if (ev != hipErrorNotSupported && ev != hipSuccess) return ev;
+  if (ev == hipErrorNotSupported) {
+    if (norm) hipLaunchKernelGGL((colreduce1_k<T, true>), grid, dim3(256), 0, s, a, lda, x, mean, rstd, kind, partial, rows, cols, rpc);
+    else hipLaunchKernelGGL((colreduce1_k<T, false>), grid, dim3(256), 0, s, a, lda, x, mean, rstd, kind, partial, rows, cols, rpc);
+  }
   SSDT_LAUNCH_CHECK();
   hipLaunchKernelGGL(colreduce2_k<T>, dim3((cols + 255) / 256), dim3(256), 0, s, (const float *)partial, chunks, cols, out_b, out_g);
   SSDT_LAUNCH_CHECK();
@@ -280,7 +288,9 @@ hipError_t norm_bwd(const void *dy, const void *x, const float *mean, const floa
                     const void *resid, void *dx, void *dgamma, void *dbeta, float *partial, int rows, int H, int kind,
                     int dtype, hipStream_t s) {
   dim3 grid((rows + 3) / 4);
-  {
+  hipError_t ev = dtype == SSDT_BF16 ? norm_bwd_dx_vec(dy, x, mean, rstd, gamma, resid, dx, rows, H, kind, s) : hipErrorNotSupported;
+  if (ev != hipErrorNotSupported && ev != hipSuccess) return ev;
+  if (ev == hipErrorNotSupported) {
     prof::Scope ps(prof::NORM_BWD, 0, (resid ? 4.0 : 3.0) * rows * H * (dtype == SSDT_F32 ? 4 : 2), s);
     if (dtype == SSDT_F32)
       hipLaunchKernelGGL(norm_bwd_dx_k<float>, grid, dim3(256), 0, s, (const float *)dy, (const float *)x, mean, rstd,

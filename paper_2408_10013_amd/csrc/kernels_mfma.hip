@@ -103,6 +103,62 @@ __device__ __forceinline__ void epilogue_block(const NtP &p, const f32x16_t &acc
   }
 }
 
+__device__ __forceinline__ void unpack8f(const uint4 &v, float *f) {
+  f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xffff0000u);
+  f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xffff0000u);
+  f[4] = __uint_as_float(v.z << 16); f[5] = __uint_as_float(v.z & 0xffff0000u);
+  f[6] = __uint_as_float(v.w << 16); f[7] = __uint_as_float(v.w & 0xffff0000u);
+}
+
+// Epilogue of a 64x64 fp32 sub-tile through LDS: the accumulators are written in MFMA layout and
+// read back row-major, so that every global access (bias, residual, activation input, outputs) is
+// 16 bytes per lane with 8 lanes covering 128 contiguous bytes of a row.  `st` is this wavefront's
+// private 64 x 68 float staging area; m_base / n_base are the sub-tile's origin.
+constexpr int kEpiLd = 68;
+template <int EPI>
+__device__ __forceinline__ void epilogue_staged(const NtP &p, const f32x16_t (&a0)[2], const f32x16_t (&a1)[2], float *st,
+                                                int m_base, int n_base, int lane) {
+  const int li = lane & 31, half = lane >> 5;
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      *(float4 *)(st + li * kEpiLd + j * 32 + g * 8 + half * 4) = make_float4(a0[j][g * 4], a0[j][g * 4 + 1], a0[j][g * 4 + 2], a0[j][g * 4 + 3]);
+      *(float4 *)(st + (32 + li) * kEpiLd + j * 32 + g * 8 + half * 4) = make_float4(a1[j][g * 4], a1[j][g * 4 + 1], a1[j][g * 4 + 2], a1[j][g * 4 + 3]);
+    }
+  const int col0 = (lane & 7) * 8, n = n_base + col0;
+  float b[8];
+#pragma unroll
+  for (int t = 0; t < 8; ++t) b[t] = 0.f;
+  if (EPI != EPI_NONE && EPI != EPI_ACTBWD && p.bias) unpack8f(*(const uint4 *)(p.bias + n), b);
+#pragma unroll
+  for (int pass = 0; pass < 8; ++pass) {
+    const int row = pass * 8 + (lane >> 3), m = m_base + row;
+    const float4 lo = *(const float4 *)(st + row * kEpiLd + col0), hi = *(const float4 *)(st + row * kEpiLd + col0 + 4);
+    float v[8] = {lo.x + b[0], lo.y + b[1], lo.z + b[2], lo.w + b[3], hi.x + b[4], hi.y + b[5], hi.z + b[6], hi.w + b[7]};
+    const long o = (long)m * p.ldc + n;
+    if (EPI == EPI_BIAS_ACT) {
+      if (p.C) *(uint4 *)(p.C + o) = make_uint4(pack_bf2(v[0], v[1]), pack_bf2(v[2], v[3]), pack_bf2(v[4], v[5]), pack_bf2(v[6], v[7]));
+#pragma unroll
+      for (int t = 0; t < 8; ++t) v[t] = p.act == SSDT_ACT_GELU ? gelu_f(v[t]) : fmaxf(v[t], 0.f);
+      *(uint4 *)(p.C2 + o) = make_uint4(pack_bf2(v[0], v[1]), pack_bf2(v[2], v[3]), pack_bf2(v[4], v[5]), pack_bf2(v[6], v[7]));
+    } else {
+      if (EPI == EPI_BIAS_RESID) {
+        float r[8];
+        unpack8f(*(const uint4 *)(p.resid + (long)m * p.ldr + n), r);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) v[t] += r[t];
+      } else if (EPI == EPI_ACTBWD) {
+        float u[8];
+        unpack8f(*(const uint4 *)(p.aux + o), u);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) v[t] *= p.act == SSDT_ACT_GELU ? gelu_grad_f(u[t]) : (u[t] > 0.f ? 1.f : 0.f);
+      }
+      *(uint4 *)(p.C + o) = make_uint4(pack_bf2(v[0], v[1]), pack_bf2(v[2], v[3]), pack_bf2(v[4], v[5]), pack_bf2(v[6], v[7]));
+    }
+  }
+}
+
 // ------------------------------------------------------------------------------------------
 // 256x256 tile, 8 wavefronts, two 64-wide LDS stages of direct global-to-LDS loads
 // ------------------------------------------------------------------------------------------
@@ -151,15 +207,15 @@ __global__ __launch_bounds__(512) void gemm_nt256_k(NtP p) {
   const uint16_t *gb = p.Bt + (long)(n0 + lrow) * p.ldb + lchunk * 8;
   const long a64 = 64 * p.lda, b64 = 64 * p.ldb;
   uint16_t *s_wave = smem + wave * 64 * 8;  // a wavefront's 64 positions are contiguous: 1 KiB per load
-#define SSDT_ISSUE(kt)                                                                                    \
+// two of the eight loads of a stage: the 64-row slices j of A and of Bt
+#define SSDT_ISSUE2(kt, j)                                                                                \
   {                                                                                                       \
-    uint16_t *sb_ = s_wave + ((kt) & 1) * kStage2;                                                        \
+    uint16_t *sb_ = s_wave + ((kt) & 1) * kStage2 + (j) * 64 * kBK2;                                      \
     const long ko_ = (long)(kt) * kBK2;                                                                   \
-    _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                       \
-      __builtin_amdgcn_global_load_lds(ga + j * a64 + ko_, (lds_void_t *)(sb_ + j * 64 * kBK2), 16, 0, 0); \
-      __builtin_amdgcn_global_load_lds(gb + j * b64 + ko_, (lds_void_t *)(sb_ + kBM2 * kBK2 + j * 64 * kBK2), 16, 0, 0); \
-    }                                                                                                     \
+    __builtin_amdgcn_global_load_lds(ga + (j) * a64 + ko_, (lds_void_t *)(sb_), 16, 0, 0);                \
+    __builtin_amdgcn_global_load_lds(gb + (j) * b64 + ko_, (lds_void_t *)(sb_ + kBM2 * kBK2), 16, 0, 0);  \
   }
+#define SSDT_ISSUE(kt) { SSDT_ISSUE2(kt, 0); SSDT_ISSUE2(kt, 1); SSDT_ISSUE2(kt, 2); SSDT_ISSUE2(kt, 3); }
 
   f32x16_t acc[4][2];
 #pragma unroll
@@ -183,30 +239,44 @@ __global__ __launch_bounds__(512) void gemm_nt256_k(NtP p) {
   const unsigned ob2 = brow + ((4 + half) ^ sw) * 16, ob3 = brow + ((6 + half) ^ sw) * 16;
   v4i_t pa0, pa1, pa2, pa3, pb0, pb1, qa0, qa1, qa2, qa3, qb0, qb1;
 
+  // The next stage's loads are spread over the four sub-steps (two per sub-step): issued in one burst they
+  // would sit in the address pipeline for ~1000 cycles and hold back the MFMAs queued behind them.
   for (int kt = 0; kt < nk; ++kt) {
     __builtin_amdgcn_s_waitcnt(0xF70);  // vmcnt(0): this wavefront's part of stage kt has landed
     __builtin_amdgcn_s_barrier();       // so has everyone's; and everyone is done reading stage kt-1
-    if (kt + 1 < nk) SSDT_ISSUE(kt + 1);
     const unsigned so = (kt & 1) * kStage2 * 2;
+    const bool more = kt + 1 < nk;
     SSDT_READ6(pa0, pa1, pa2, pa3, pb0, pb1, oa0 + so, ob0 + so);
     SSDT_READ6(qa0, qa1, qa2, qa3, qb0, qb1, oa1 + so, ob1 + so);
     SSDT_WAIT6(6, pa0, pa1, pa2, pa3, pb0, pb1);
+    if (more) SSDT_ISSUE2(kt + 1, 0);
+    __builtin_amdgcn_sched_barrier(0);
     SSDT_MFMA8(pa0, pa1, pa2, pa3, pb0, pb1);
+    __builtin_amdgcn_sched_barrier(0);
     SSDT_READ6(pa0, pa1, pa2, pa3, pb0, pb1, oa2 + so, ob2 + so);
     SSDT_WAIT6(6, qa0, qa1, qa2, qa3, qb0, qb1);
+    if (more) SSDT_ISSUE2(kt + 1, 1);
+    __builtin_amdgcn_sched_barrier(0);
     SSDT_MFMA8(qa0, qa1, qa2, qa3, qb0, qb1);
+    __builtin_amdgcn_sched_barrier(0);
     SSDT_READ6(qa0, qa1, qa2, qa3, qb0, qb1, oa3 + so, ob3 + so);
     SSDT_WAIT6(6, pa0, pa1, pa2, pa3, pb0, pb1);
+    if (more) SSDT_ISSUE2(kt + 1, 2);
+    __builtin_amdgcn_sched_barrier(0);
     SSDT_MFMA8(pa0, pa1, pa2, pa3, pb0, pb1);
+    __builtin_amdgcn_sched_barrier(0);
     SSDT_WAIT6(0, qa0, qa1, qa2, qa3, qb0, qb1);
+    if (more) SSDT_ISSUE2(kt + 1, 3);
+    __builtin_amdgcn_sched_barrier(0);
     SSDT_MFMA8(qa0, qa1, qa2, qa3, qb0, qb1);
   }
+#undef SSDT_ISSUE2
 #undef SSDT_ISSUE
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-      epilogue_block<EPI>(p, acc[i][j], m0 + wm * 128 + i * 32 + li, n0 + wn * 64 + j * 32 + half * 4);
+  // epilogue through LDS (free now), two 64-row halves of the wavefront's 128x64 tile
+  __builtin_amdgcn_s_barrier();  // every wavefront has finished reading the last stage
+  float *stg = (float *)smem + wave * (64 * kEpiLd);
+  epilogue_staged<EPI>(p, acc[0], acc[1], stg, m0 + wm * 128, n0 + wn * 64, lane);
+  epilogue_staged<EPI>(p, acc[2], acc[3], stg, m0 + wm * 128 + 64, n0 + wn * 64, lane);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -291,7 +361,7 @@ __global__ __launch_bounds__(256) void gemm_nt128_k(NtP p) {
 
 template <int EPI>
 static hipError_t launch256(const NtP &p, hipStream_t s) {
-  constexpr size_t smem = (size_t)2 * kStage2 * 2;
+  constexpr size_t smem = (size_t)8 * 64 * kEpiLd * 4 > (size_t)2 * kStage2 * 2 ? (size_t)8 * 64 * kEpiLd * 4 : (size_t)2 * kStage2 * 2;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void *)gemm_nt256_k<EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -376,9 +446,11 @@ hipError_t gemm_mfma_bf16(const Gemm &g, hipStream_t s) {
   if (!al16(A) || !al16(Bt) || lda % 8 || ldb % 8) return hipErrorNotSupported;
   NtP p{g.M, g.N, g.K, A, Bt, lda, ldb, g.ldc, g.ldr, (uint16_t *)g.C, (uint16_t *)g.C2, (const uint16_t *)g.bias,
         (const uint16_t *)g.resid, (const uint16_t *)g.aux, g.act, 0, 0};
-  bool big = (g.M % 256 == 0) && (g.N % 256 == 0) && ((long)(g.M / 256) * (g.N / 256) >= 256);
+  const bool epi16 = g.ldc % 8 == 0 && al16(g.C) && (!g.C2 || al16(g.C2)) && (!g.bias || al16(g.bias)) &&
+                     (!g.aux || al16(g.aux)) && (!g.resid || (al16(g.resid) && g.ldr % 8 == 0));
+  bool big = epi16 && (g.M % 256 == 0) && (g.N % 256 == 0) && ((long)(g.M / 256) * (g.N / 256) >= 256);
   if (g_force_tile == 128) big = false;
-  if (g_force_tile == 256 && g.M % 256 == 0 && g.N % 256 == 0) big = true;
+  if (g_force_tile == 256 && epi16 && g.M % 256 == 0 && g.N % 256 == 0) big = true;
   const int t = big ? 256 : 128;
   p.tiles_m = g.M / t;
   p.tiles_n = g.N / t;
