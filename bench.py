@@ -96,6 +96,8 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="0 = the configuration's own")
     ap.add_argument("--modes", default="off,all,budget")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep", default="", help="comma-separated micro-batch sizes: one off/budget measurement per size "
+                                                "(throughput and activation memory vs micro-batch), printed as one JSON line")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (one process, one MI355X, no collectives); "
@@ -112,101 +114,122 @@ def main():
         sys.exit(1)
     dev = torch.device("cuda:0")
     cfg = synth.CONFIGS[args.workload]
-    B = args.micro_batch or cfg["B"]
-    layers = runner.layers_from_config(cfg, B=B, n_layers=args.layers or None)
-    L = len(layers)
     dtype = cfg["dtype"]
     tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    weights_cache = {}
 
-    # seeded synthetic weights and inputs, generated on the device
-    gen = torch.Generator(device=dev)
-    gen.manual_seed(synth.BASE_SEED + cfg["index"])
-    for l in layers:
-        w = {}
-        for name, shp in l.shapes.items():
-            if name.startswith("w_"):
-                w[name] = (torch.randn(shp, generator=gen, device=dev, dtype=torch.float32) * 0.02).to(tdt)
-            elif name.endswith("_g"):
-                w[name] = torch.ones(shp, device=dev, dtype=tdt)
-            else:
-                w[name] = torch.zeros(shp, device=dev, dtype=tdt)
-        l.set_weights(w)
-    first_dec = next((l for l in layers if l.arch != "t5_enc"), layers[0])
-    x = torch.randn(first_dec.T, first_dec.H, generator=gen, device=dev, dtype=torch.float32).to(tdt)
-    dy = torch.randn(first_dec.T, first_dec.H, generator=gen, device=dev, dtype=torch.float32).to(tdt)
-    enc_x = None
-    if layers[0].arch == "t5_enc":
-        enc_x = torch.randn(layers[0].T, layers[0].H, generator=gen, device=dev, dtype=torch.float32).to(tdt)
-    kv_len = None
-    if cfg.get("kv_len_range"):
-        lo_, hi_ = cfg["kv_len_range"]
-        kv_len = torch.from_numpy(np.random.default_rng(synth.BASE_SEED).integers(lo_, hi_ + 1, size=B).astype(np.int32)).to(dev)
+    def measure(B, want):
+        layers = runner.layers_from_config(cfg, B=B, n_layers=args.layers or None)
+        L = len(layers)
+        # seeded synthetic weights and inputs, generated on the device (weights are the same for every B)
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(synth.BASE_SEED + cfg["index"])
+        for li, l in enumerate(layers):
+            if li not in weights_cache:
+                w = {}
+                for name, shp in l.shapes.items():
+                    if name.startswith("w_"):
+                        w[name] = (torch.randn(shp, generator=gen, device=dev, dtype=torch.float32) * 0.02).to(tdt)
+                    elif name.endswith("_g"):
+                        w[name] = torch.ones(shp, device=dev, dtype=tdt)
+                    else:
+                        w[name] = torch.zeros(shp, device=dev, dtype=tdt)
+                weights_cache[li] = w
+            l.set_weights(weights_cache[li])
+        first_dec = next((l for l in layers if l.arch != "t5_enc"), layers[0])
+        x = torch.randn(first_dec.T, first_dec.H, generator=gen, device=dev, dtype=torch.float32).to(tdt)
+        dy = torch.randn(first_dec.T, first_dec.H, generator=gen, device=dev, dtype=torch.float32).to(tdt)
+        enc_x = None
+        if layers[0].arch == "t5_enc":
+            enc_x = torch.randn(layers[0].T, layers[0].H, generator=gen, device=dev, dtype=torch.float32).to(tdt)
+        kv_len = None
+        if cfg.get("kv_len_range"):
+            lo_, hi_ = cfg["kv_len_range"]
+            kv_len = torch.from_numpy(np.random.default_rng(synth.BASE_SEED).integers(lo_, hi_ + 1, size=B).astype(np.int32)).to(dev)
 
-    per_layer = [runner.saved_bytes_per_layer(l) for l in layers]
-    full = sum(per_layer) + max(per_layer) + (64 << 20)   # every layer resident, plus slack
-    link = link_rate(torch, dev)
-    flops = stack_flops(layers, kv_len.cpu().numpy() if kv_len is not None else None)
-    setup = {}
+        per_layer = [runner.saved_bytes_per_layer(l) for l in layers]
+        full = sum(per_layer) + max(per_layer) + (64 << 20)   # every layer resident, plus slack
+        flops = stack_flops(layers, kv_len.cpu().numpy() if kv_len is not None else None)
+        setup = {}
 
-    def run_mode(name, budget, arena_bytes, pool_bytes, profile=False):
-        """One context per mode: the arena size is what bounds the activation memory of that mode."""
-        t0 = time.perf_counter()
-        st = runner.Stack(layers, arena_bytes, pool_bytes, "cuda:0", keep_last=1, min_offload_elems=1 << 20,
-                          budget_bytes=budget, measure_waits=1)
-        st.register_weights()
-        setup[name] = time.perf_counter() - t0
+        def run_mode(name, budget, arena_bytes, pool_bytes, profile=False):
+            """One context per mode: the arena size is what bounds the activation memory of that mode."""
+            t0 = time.perf_counter()
+            st = runner.Stack(layers, arena_bytes, pool_bytes, "cuda:0", keep_last=1, min_offload_elems=1 << 20,
+                              budget_bytes=budget, measure_waits=1)
+            st.register_weights()
+            setup[name] = time.perf_counter() - t0
 
-        def step():
-            y = st.forward(x, enc_x=enc_x, kv_len=kv_len)
-            st.backward(dy)
-            sb.ssdt_arena_free(st.ctx, y, st.stream)
+            def step():
+                y = st.forward(x, enc_x=enc_x, kv_len=kv_len)
+                st.backward(dy)
+                sb.ssdt_arena_free(st.ctx, y, st.stream)
 
-        for _ in range(args.warmup):
-            step()
-        torch.cuda.synchronize()
-        sb.ssdt_sync_io(st.ctx)
-        if profile:
-            sb.ssdt_profile(st.ctx, True)
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            step()
-        torch.cuda.synchronize()
-        dt = (time.perf_counter() - t0) / args.steps
+            for _ in range(args.warmup):
+                step()
+            torch.cuda.synchronize()
+            sb.ssdt_sync_io(st.ctx)
+            if profile:
+                sb.ssdt_profile(st.ctx, True)
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                step()
+            torch.cuda.synchronize()
+            dt = (time.perf_counter() - t0) / args.steps
+            prof = None
+            if profile:
+                prof = sb.ssdt_profile_read(st.ctx)
+                sb.ssdt_profile(st.ctx, False)
+            s = st.stats()
+            st.close()
+            del st
+            torch.cuda.empty_cache()
+            return dict(ms_per_step=dt * 1e3, tflops=flops / dt / 1e12, arena_bytes=arena_bytes,
+                        bytes_offloaded=s["bytes_offloaded"], bytes_kept=s["bytes_kept"], bytes_loaded=s["bytes_loaded"],
+                        forwarded=s["forwarded"], loads=s["loads"], arena_peak_bytes=s["arena_peak_in_use"],
+                        exposed_load_wait_ms=s["exposed_load_wait_ns"] / 1e6,
+                        exposed_store_wait_ms=s["exposed_store_wait_ns"] / 1e6,
+                        link_GBps=(s["bytes_offloaded"] + s["bytes_loaded"]) / dt / 1e9), prof
+
+        modes = {}
         prof = None
-        if profile:
-            prof = sb.ssdt_profile_read(st.ctx)
-            sb.ssdt_profile(st.ctx, False)
-        s = st.stats()
-        st.close()
-        del st
-        torch.cuda.empty_cache()
-        return dict(ms_per_step=dt * 1e3, tflops=flops / dt / 1e12, arena_bytes=arena_bytes,
-                    bytes_offloaded=s["bytes_offloaded"], bytes_kept=s["bytes_kept"], bytes_loaded=s["bytes_loaded"],
-                    forwarded=s["forwarded"], loads=s["loads"], arena_peak_bytes=s["arena_peak_in_use"],
-                    exposed_load_wait_ms=s["exposed_load_wait_ns"] / 1e6,
-                    exposed_store_wait_ms=s["exposed_store_wait_ns"] / 1e6,
-                    link_GBps=(s["bytes_offloaded"] + s["bytes_loaded"]) / dt / 1e9), prof
+        modes["off"], prof = run_mode("off", 0, full, 0, profile=("budget" not in want))
+        if "all" in want:
+            # three layers' worth of arena: the layer computing, the one being stored / loaded, and slack
+            modes["all"], _ = run_mode("all", -1, 3 * max(per_layer) + (64 << 20), runner.pool_bytes_needed(layers))
+        if "budget" in want:
+            # offload amount the link can drain while the forward runs (Sec. 3.1: the amount is set from the amount
+            # of computation, the activation size, the GPU throughput and the I/O bandwidth); the arena shrinks by
+            # what is expected to have left the device by the end of the forward pass
+            t_fwd = modes["off"]["ms_per_step"] * 1e-3 / 3.0
+            budget = int(min(0.85 * link["d2h"] * 1e9 * t_fwd, sum(per_layer[:-1])))
+            arena = modes["off"]["arena_peak_bytes"] + (256 << 20) + max(per_layer) // 4 - int(0.75 * budget)
+            modes["budget"], prof = run_mode("budget", budget, arena, budget + (256 << 20), profile=True)
+            modes["budget"]["budget_bytes"] = budget
+        for k, m in modes.items():
+            m["exposed_io_pct"] = max(0.0, (m["ms_per_step"] - modes["off"]["ms_per_step"]) / m["ms_per_step"] * 100.0)
+            m["arena_peak_vs_off"] = m["arena_peak_bytes"] / max(1, modes["off"]["arena_peak_bytes"])
+        return layers, modes, prof, setup
 
-    modes = {}
-    want = args.modes.split(",")
-    prof = None
-    modes["off"], prof = run_mode("off", 0, full, 0, profile=("budget" not in want))
-    if "all" in want:
-        # three layers' worth of arena: the layer computing, the one being stored / loaded, and slack
-        modes["all"], _ = run_mode("all", -1, 3 * max(per_layer) + (64 << 20), runner.pool_bytes_needed(layers))
-    if "budget" in want:
-        # offload amount the link can drain while the forward runs (Sec. 3.1: the amount is set from the
-        # amount of computation, the activation size, the GPU throughput and the I/O bandwidth); the
-        # arena shrinks by what is expected to have left the device by the end of the forward pass
-        t_fwd = modes["off"]["ms_per_step"] * 1e-3 / 3.0
-        budget = int(min(0.85 * link["d2h"] * 1e9 * t_fwd, sum(per_layer[:-1])))
-        arena = modes["off"]["arena_peak_bytes"] + (256 << 20) - int(0.8 * budget)
-        modes["budget"], prof = run_mode("budget", budget, arena, budget + (256 << 20), profile=True)
-        modes["budget"]["budget_bytes"] = budget
+    link = link_rate(torch, dev)
+    if args.sweep:
+        rows = []
+        for B in [int(v) for v in args.sweep.split(",")]:
+            _, modes, _, _ = measure(B, ["off", "budget"])
+            rows.append({"micro_batch": B, "off_tflops": modes["off"]["tflops"], "off_ms": modes["off"]["ms_per_step"],
+                         "off_activation_bytes": modes["off"]["arena_peak_bytes"],
+                         "budget_tflops": modes["budget"]["tflops"], "budget_ms": modes["budget"]["ms_per_step"],
+                         "budget_activation_bytes": modes["budget"]["arena_peak_bytes"],
+                         "budget_offloaded_bytes": modes["budget"]["bytes_offloaded"],
+                         "budget_exposed_io_pct": modes["budget"]["exposed_io_pct"]})
+        print(json.dumps({"metric": "layer fwd+bwd TFLOP/s vs micro-batch (off / adaptive offload)", "unit": "TFLOP/s",
+                          "workload": args.workload, "steps": args.steps, "warmup": args.warmup, "dtype": dtype,
+                          "data": "synthetic", "link_measured_GBps": link, "sweep": rows}))
+        return
+    B = args.micro_batch or cfg["B"]
+    layers, modes, prof, setup = measure(B, args.modes.split(","))
+    L = len(layers)
     head = modes.get("budget") or modes["off"]
-    for k, m in modes.items():
-        m["exposed_io_pct"] = max(0.0, (m["ms_per_step"] - modes["off"]["ms_per_step"]) / m["ms_per_step"] * 100.0)
-        m["arena_peak_vs_off"] = m["arena_peak_bytes"] / max(1, modes["off"]["arena_peak_bytes"])
 
     roof = None
     if prof:

@@ -42,12 +42,14 @@ class HipBackend : public Backend {
     if (pool_) (void)hipHostFree(pool_);
   }
   bool is_sim() const override { return false; }
+  uint64_t seq_ = 0;
   Ev *get_ev(bool timing) {
     auto &fl = free_[timing ? 1 : 0];
     if (!fl.empty()) {
       Ev *e = fl.back();
       fl.pop_back();
       e->refs = 0;
+      e->seq = ++seq_;
       return e;
     }
     Ev *e = new Ev();
@@ -55,6 +57,7 @@ class HipBackend : public Backend {
     hipEvent_t h;
     check(hipEventCreateWithFlags(&h, timing ? hipEventDefault : hipEventDisableTiming), "hipEventCreate");
     e->h = h;
+    e->seq = ++seq_;
     all_.push_back(e);
     return e;
   }

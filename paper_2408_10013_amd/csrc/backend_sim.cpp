@@ -20,6 +20,7 @@ class SimBackend : public Backend {
   std::deque<Job> q_[2];
   void *pool_ = nullptr;
   std::vector<Ev *> all_, free_;
+  uint64_t seq_ = 0;
   int tag_[2] = {0, 0};  // addresses of these stand for the two queues
 
   ~SimBackend() override {
@@ -38,6 +39,7 @@ class SimBackend : public Backend {
     }
     e->refs = 0;
     e->done = true;
+    e->seq = ++seq_;
     return e;
   }
   Ev *record(ssdt_stream, bool) override { return get_ev(); }

@@ -27,6 +27,7 @@ struct Ev {
   bool done = true;
   bool timing = false;
   int refs = 0;  // holders: free blocks, records, pending wait measurements
+  uint64_t seq = 0;  // order of creation: on one in-order stream a younger event implies every older one
 };
 
 // What the registry needs from the machine: events, cross-stream waits and the two

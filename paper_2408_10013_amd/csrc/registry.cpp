@@ -46,8 +46,20 @@ static void tidy(Ctx *c) {
   }
   for (auto it = c->blocks.begin(); it != c->blocks.end();) {
     auto nx = std::next(it);
-    if (nx != c->blocks.end() && it->second.free && nx->second.free && !it->second.ready && !nx->second.ready) {
-      it->second.size += nx->second.size;
+    if (nx == c->blocks.end()) break;
+    Block &a = it->second, &b = nx->second;
+    // neighbours merge when one event covers both: none at all, only one of them has one, or both
+    // wait on the same in-order stream (then the younger event implies the older)
+    bool ok = a.free && b.free && (!a.ready || !b.ready || a.ready_stream == b.ready_stream);
+    if (ok) {
+      if (b.ready && (!a.ready || b.ready->seq > a.ready->seq)) {
+        drop(c->be.get(), a.ready);
+        a.ready = b.ready;  // takes over b's reference
+        a.ready_stream = b.ready_stream;
+      } else {
+        drop(c->be.get(), b.ready);
+      }
+      a.size += b.size;
       c->blocks.erase(nx);
     } else {
       it = nx;
@@ -55,32 +67,51 @@ static void tidy(Ctx *c) {
   }
 }
 
+// Large blocks are placed first-fit from the bottom of the arena, small ones (statistics, a few
+// KiB each and long-lived) from the top, so that the small ones do not end up between large
+// blocks and keep their neighbours from merging once those are freed.
 bool Ctx::try_alloc(size_t bytes, ssdt_stream s, void **out) {
-  for (auto it = blocks.begin(); it != blocks.end(); ++it) {
-    Block &b = it->second;
-    if (!b.free || b.size < bytes) continue;
-    if (b.size > bytes) {
-      Block rest = b;
-      rest.size = b.size - bytes;
-      hold(rest.ready);
-      blocks[it->first + bytes] = rest;
-      b.size = bytes;
+  const bool small = bytes < (1u << 20);
+  std::map<size_t, Block>::iterator hit = blocks.end();
+  if (!small) {
+    for (auto it = blocks.begin(); it != blocks.end(); ++it)
+      if (it->second.free && it->second.size >= bytes) { hit = it; break; }
+  } else {
+    for (auto it = blocks.end(); it != blocks.begin();) {
+      --it;
+      if (it->second.free && it->second.size >= bytes) { hit = it; break; }
     }
-    if (b.ready) {
-      if (b.ready_stream != s) be->wait(s, b.ready);
-      drop(be.get(), b.ready);
-      b.ready = nullptr;
-    }
-    b.free = false;
-    b.refs = 1;
-    in_use += bytes;
-    peak_in_use = std::max(peak_in_use, in_use);
-    high_water = std::max<uint64_t>(high_water, it->first + bytes);
-    ++n_allocs;
-    *out = (char *)cfg.arena_base + it->first;
-    return true;
   }
-  return false;
+  if (hit == blocks.end()) return false;
+  if (hit->second.size > bytes) {
+    Block rest = hit->second;
+    rest.size = hit->second.size - bytes;
+    hold(rest.ready);
+    if (!small) {  // keep the low part
+      blocks[hit->first + bytes] = rest;
+      hit->second.size = bytes;
+    } else {       // keep the high part
+      Block mine = hit->second;
+      mine.size = bytes;
+      const size_t off = hit->first + rest.size;
+      hit->second = rest;
+      hit = blocks.emplace(off, mine).first;
+    }
+  }
+  Block &b = hit->second;
+  if (b.ready) {
+    if (b.ready_stream != s) be->wait(s, b.ready);
+    drop(be.get(), b.ready);
+    b.ready = nullptr;
+  }
+  b.free = false;
+  b.refs = 1;
+  in_use += bytes;
+  peak_in_use = std::max(peak_in_use, in_use);
+  high_water = std::max<uint64_t>(high_water, hit->first + bytes);
+  ++n_allocs;
+  *out = (char *)cfg.arena_base + hit->first;
+  return true;
 }
 
 ssdt_status Ctx::alloc(size_t bytes, ssdt_stream s, void **out) {
