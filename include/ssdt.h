@@ -79,8 +79,16 @@ typedef struct ssdt_config {
   void *arena_base;           /* DEVICE, 256-byte aligned: activation arena the library sub-allocates */
   size_t arena_bytes;
   size_t pool_bytes;          /* pinned host pool, allocated once at create (Sec. 3.1, CPU offloader) */
-  const char *spill_path;     /* HOST string or NULL: if set, each completed pack is also written to this
-                                 file and read back from it before its prefetch */
+  const char *spill_path;     /* HOST string or NULL.  If set (Sec. 3.1, SSD offloader): the file is created
+                                 or truncated at create (SSDT_E_IO if that fails) and becomes the store,
+                                 the pool its staging buffer.  A worker thread writes every offloaded
+                                 tensor to the file, at its pool offset, once its copy out of the device
+                                 has completed, and then overwrites the tensor's pool bytes; a prefetch
+                                 reads the tensor back into the pool, and the copy into the device is
+                                 enqueued by the first later call on the context that finds the read
+                                 complete (ssdt_get blocks the host for it if need be).  A failed
+                                 read or write makes the next ssdt_offload / ssdt_prefetch / ssdt_get /
+                                 ssdt_sync_io / ssdt_step_begin return SSDT_E_IO. */
   int32_t measure_waits;      /* nonzero: bracket every wait of a compute stream on a load with timing
                                  events so that ssdt_get_stats can report exposed I/O time */
   int32_t reserved;
@@ -192,13 +200,18 @@ ssdt_status ssdt_get_stats(ssdt_ctx *ctx, ssdt_stats *out);
 ssdt_status ssdt_num_records(const ssdt_ctx *ctx, uint32_t *out);
 ssdt_status ssdt_get_record(const ssdt_ctx *ctx, uint32_t index, ssdt_record *out); /* in first-save order */
 /* Copies `bytes` of the host pool starting at `pool_offset` into `dst` (HOST); waits for the store
- * stream first.  For tests of the reload-is-bit-identical invariant. */
+ * stream first.  With a spill file it waits for the pending file writes too and reads the file
+ * instead.  For tests of the reload-is-bit-identical invariant. */
 ssdt_status ssdt_pool_read(ssdt_ctx *ctx, size_t pool_offset, void *dst, size_t bytes);
 /* SIM backend only: performs the next `n` queued copies of direction 0 (store) or 1 (load), in
  * order, and marks them complete.  `*done` = number performed. */
 ssdt_status ssdt_sim_complete(ssdt_ctx *ctx, int32_t direction, int32_t n, int32_t *done);
-/* Blocks the host until the store and load streams are idle. */
+/* Blocks the host until the store and load streams are idle and, with a spill file, until every
+ * file write and read requested so far has been done. */
 ssdt_status ssdt_sync_io(ssdt_ctx *ctx);
+/* Bytes written to and read from the spill file since create (either pointer may be NULL, HOST).
+ * SSDT_E_STATE if the context has no spill file. */
+ssdt_status ssdt_spill_stats(ssdt_ctx *ctx, uint64_t *bytes_written, uint64_t *bytes_read);
 
 /* ---- kernel timing ------------------------------------------------------------------------ */
 

@@ -112,6 +112,7 @@ _PROTOS = {
     "ssdt_pool_read": (C.c_int32, [C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t]),
     "ssdt_sim_complete": (C.c_int32, [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_int32)]),
     "ssdt_sync_io": (C.c_int32, [C.c_void_p]),
+    "ssdt_spill_stats": (C.c_int32, [C.c_void_p, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)]),
     "ssdt_profile": (C.c_int32, [C.c_void_p, C.c_int32]),
     "ssdt_profile_read": (C.c_int32, [C.c_void_p, C.POINTER(ssdt_kernel_time), C.c_uint32, C.POINTER(C.c_uint32)]),
     "ssdt_layer_workspace": (C.c_int32, [C.POINTER(ssdt_layer_desc), C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]),
@@ -258,6 +259,12 @@ def ssdt_sim_complete(ctx, direction, n) -> int:
 
 def ssdt_sync_io(ctx):
     _check(ctx, lib().ssdt_sync_io(ctx), "ssdt_sync_io")
+
+
+def ssdt_spill_stats(ctx):
+    w, r = C.c_uint64(0), C.c_uint64(0)
+    _check(ctx, lib().ssdt_spill_stats(ctx, C.byref(w), C.byref(r)), "ssdt_spill_stats")
+    return w.value, r.value
 
 
 def ssdt_profile(ctx, enable: bool):

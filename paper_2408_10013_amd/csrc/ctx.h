@@ -5,7 +5,10 @@
 #include <cstdint>
 #include <cstdio>
 #include <cstring>
+#include <condition_variable>
 #include <deque>
+#include <mutex>
+#include <thread>
 #include <map>
 #include <memory>
 #include <string>
@@ -73,11 +76,33 @@ struct Rec {
   bool forwarded = false;
   bool release_pending = false;  // released while its store was still in flight
   bool load_waited = false;
+  bool spill_deferred = false; // spill mode: dropped from the device before its copy out was seen finished
+  bool read_pending = false;  // spill mode: the file read of this record has been requested, its copy not yet issued
   std::vector<int32_t> scopes;
   Ev *store_ev = nullptr, *load_ev = nullptr;
 };
 
 struct WaitPair { Ev *a, *b; int kind; };
+
+// Spill file: the tier behind the pinned pool (Sec. 3.1 names an SSD offloader beside the CPU
+// offloader).  The pool is the staging buffer, the file holds the data at the same offsets.  One
+// worker thread serves requests in order: a record is written once its device-to-host copy has
+// completed (its pool bytes are then overwritten with a pattern, so a later load can only come
+// from the file), and read back into the pool when a prefetch asks for it.  The host-to-device
+// copy of a record is issued by the next API call that finds its read complete.
+struct Spill {
+  int fd = -1;
+  std::thread worker;
+  std::mutex mu;
+  std::condition_variable cv;
+  struct Job { int kind; size_t off, bytes; };  // kind 0 write, 1 read
+  std::deque<Job> jobs;
+  std::map<size_t, int> state;   // pool offset -> 1 write queued, 2 written, 3 read queued, 4 in pool again
+  bool busy = false, stop = false;
+  std::string error;             // first I/O error, sticky
+  uint64_t bytes_written = 0, bytes_read = 0;
+  char *pool = nullptr;
+};
 
 struct Ctx {
   ssdt_config cfg{};
@@ -100,6 +125,8 @@ struct Ctx {
   std::deque<size_t> storing;  // record indices with a store in flight, oldest first
   ssdt_stats st{};
   std::vector<WaitPair> waits;
+  std::unique_ptr<Spill> spill;
+  std::deque<size_t> spill_wait, reading;  // records waiting for their file write / file read
 
   ssdt_status fail(ssdt_status code, const char *fmt, ...);
   bool in_arena(const void *p) const {
@@ -125,6 +152,15 @@ struct Ctx {
   ssdt_status release(int32_t scope, ssdt_stream s);
   ssdt_status step_begin(int32_t n);
   void timed_wait(ssdt_stream s, Ev *e, int kind);
+  ssdt_status spill_open(const char *path);
+  void spill_close();
+  ssdt_status spill_status(const char *who);
+  void spill_request(int kind, size_t pool_off, size_t bytes);
+  bool spill_in_pool(size_t pool_off, bool block);
+  void spill_drain();
+  ssdt_status start_load(size_t idx, const char *who);
+  ssdt_status issue_copy_in(size_t idx, const char *who);
+  ssdt_status pump_reads();
 };
 
 }  // namespace ssdt

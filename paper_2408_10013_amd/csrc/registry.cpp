@@ -8,6 +8,10 @@
 #include <algorithm>
 
 #include "ctx.h"
+
+#include <cerrno>
+#include <fcntl.h>
+#include <unistd.h>
 #include "prof.h"
 
 namespace ssdt {
@@ -187,6 +191,166 @@ void Ctx::reclaim(size_t idx) {
   }
   r.dev = nullptr;
   r.state = r.release_pending ? SSDT_ST_RELEASED : SSDT_ST_OFFLOADED;
+  if (spill && !r.release_pending) {
+    if (finished) {
+      spill_request(0, (size_t)r.pool_offset, r.bytes);
+    } else {  // written once the copy is seen finished
+      r.spill_deferred = true;
+      spill_wait.push_back(idx);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// spill file
+// ---------------------------------------------------------------------------------------
+
+static bool rw_all(int fd, char *buf, size_t n, size_t off, bool write, std::string *err) {
+  while (n) {
+    ssize_t k = write ? pwrite(fd, buf, n, (off_t)off) : pread(fd, buf, n, (off_t)off);
+    if (k < 0 && errno == EINTR) continue;
+    if (k <= 0) {
+      *err = std::string(write ? "spill write: " : "spill read: ") + (k == 0 ? "unexpected end of file" : strerror(errno));
+      return false;
+    }
+    buf += k;
+    off += (size_t)k;
+    n -= (size_t)k;
+  }
+  return true;
+}
+
+static void spill_worker(Spill *sp) {
+  std::unique_lock<std::mutex> lk(sp->mu);
+  for (;;) {
+    sp->cv.wait(lk, [&] { return sp->stop || !sp->jobs.empty(); });
+    if (sp->jobs.empty()) return;  // stop requested and nothing left
+    Spill::Job j = sp->jobs.front();
+    sp->jobs.pop_front();
+    sp->busy = true;
+    bool failed = !sp->error.empty();
+    lk.unlock();
+    std::string err;
+    bool ok = true;
+    if (!failed) {
+      ok = rw_all(sp->fd, sp->pool + j.off, j.bytes, j.off, j.kind == 0, &err);
+      if (ok && j.kind == 0) memset(sp->pool + j.off, 0xEE, j.bytes);  // from here on only the file has it
+    }
+    lk.lock();
+    if (!ok && sp->error.empty()) sp->error = err;
+    if (ok && !failed) (j.kind == 0 ? sp->bytes_written : sp->bytes_read) += j.bytes;
+    sp->state[j.off] = j.kind == 0 ? 2 : 4;
+    sp->busy = false;
+    sp->cv.notify_all();
+  }
+}
+
+ssdt_status Ctx::spill_open(const char *path) {
+  int fd = open(path, O_RDWR | O_CREAT | O_TRUNC, 0600);
+  if (fd < 0) return fail(SSDT_E_IO, "cannot open the spill file %s: %s", path, strerror(errno));
+  spill.reset(new Spill());
+  spill->fd = fd;
+  spill->pool = (char *)be->pool();
+  spill->worker = std::thread(spill_worker, spill.get());
+  return SSDT_OK;
+}
+
+void Ctx::spill_close() {
+  if (!spill) return;
+  {
+    std::lock_guard<std::mutex> g(spill->mu);
+    spill->stop = true;
+  }
+  spill->cv.notify_all();
+  spill->worker.join();
+  close(spill->fd);
+  spill.reset();
+}
+
+void Ctx::spill_request(int kind, size_t off, size_t bytes) {
+  {
+    std::lock_guard<std::mutex> g(spill->mu);
+    spill->jobs.push_back({kind, off, bytes});
+    spill->state[off] = kind == 0 ? 1 : 3;
+  }
+  spill->cv.notify_all();
+}
+
+// True once the bytes at `off` have been read back into the pool; with `block`, waits for that.
+bool Ctx::spill_in_pool(size_t off, bool block) {
+  std::unique_lock<std::mutex> lk(spill->mu);
+  if (block) spill->cv.wait(lk, [&] { return spill->state[off] == 4; });
+  return spill->state[off] == 4;
+}
+
+void Ctx::spill_drain() {
+  std::unique_lock<std::mutex> lk(spill->mu);
+  spill->cv.wait(lk, [&] { return spill->jobs.empty() && !spill->busy; });
+}
+
+ssdt_status Ctx::spill_status(const char *who) {
+  if (!spill) return SSDT_OK;
+  std::lock_guard<std::mutex> g(spill->mu);
+  if (spill->error.empty()) return SSDT_OK;
+  return fail(SSDT_E_IO, "%s: %s", who, spill->error.c_str());
+}
+
+// Enqueues the host-to-device copy of record idx from the pool into its (already assigned) slot.
+ssdt_status Ctx::issue_copy_in(size_t idx, const char *who) {
+  Rec &r = recs[idx];
+  r.read_pending = false;
+  // a record dropped under memory pressure may still be on its way out: the copy in follows it
+  Ev *after = (r.store_ev && !be->done(r.store_ev)) ? r.store_ev : nullptr;
+  drop(be.get(), r.load_ev);
+  r.load_ev = hold(be->copy(1, r.dev, (char *)be->pool() + r.pool_offset, r.bytes, after));
+  if (!be->err.empty()) return fail(SSDT_E_HIP, "%s: %s", who, be->err.c_str());
+  return SSDT_OK;
+}
+
+// Starts bringing an OFFLOADED record, whose new slot is already in r.dev, back to the device.
+ssdt_status Ctx::start_load(size_t idx, const char *who) {
+  Rec &r = recs[idx];
+  r.state = SSDT_ST_LOADING;
+  r.load_waited = false;
+  ++st.loads;
+  st.bytes_loaded += r.bytes;
+  if (spill && !r.spill_deferred) {  // only the file has the bytes: read first, copy when that is done
+    drop(be.get(), r.load_ev);
+    r.load_ev = nullptr;
+    r.read_pending = true;
+    reading.push_back(idx);
+    spill_request(1, (size_t)r.pool_offset, r.bytes);
+    return SSDT_OK;
+  }
+  r.spill_deferred = false;  // taken straight from the pool; its write to the file is dropped
+  return issue_copy_in(idx, who);
+}
+
+// Spill mode housekeeping: queue the writes of stores seen finished, issue the copies of finished reads.
+ssdt_status Ctx::pump_reads() {
+  if (!spill) return SSDT_OK;
+  while (!spill_wait.empty()) {
+    Rec &r = recs[spill_wait.front()];
+    if (r.spill_deferred) {
+      if (!be->done(r.store_ev)) break;  // stores finish in order
+      r.spill_deferred = false;
+      if (r.state == SSDT_ST_OFFLOADED) spill_request(0, (size_t)r.pool_offset, r.bytes);
+    }
+    spill_wait.pop_front();
+  }
+  while (!reading.empty()) {
+    size_t idx = reading.front();
+    Rec &r = recs[idx];
+    if (r.read_pending) {
+      if (!spill_in_pool((size_t)r.pool_offset, false)) break;  // reads finish in order
+      ssdt_status e = spill_status("load");
+      if (e != SSDT_OK) return e;
+      e = issue_copy_in(idx, "load");
+      if (e != SSDT_OK) return e;
+    }
+    reading.pop_front();
+  }
+  return SSDT_OK;
 }
 
 void Ctx::poll() {
@@ -201,6 +365,7 @@ void Ctx::poll() {
     storing.pop_front();
     reclaim(idx);
   }
+  if (spill) (void)pump_reads();  // an I/O error stays recorded and is reported by spill_status()
 }
 
 ssdt_status Ctx::step_begin(int32_t n) {
@@ -214,6 +379,14 @@ ssdt_status Ctx::step_begin(int32_t n) {
   if (!storing.empty()) {
     be->sync_io();
     poll();
+  }
+  if (spill) {
+    spill_drain();
+    spill->state.clear();
+    spill_wait.clear();
+    reading.clear();
+    ssdt_status e = spill_status("step_begin");
+    if (e != SSDT_OK) return e;
   }
   for (auto &r : recs) {
     drop(be.get(), r.store_ev);
@@ -352,6 +525,7 @@ ssdt_status Ctx::save(const void *base, size_t sbytes, size_t view_off, const in
 
 ssdt_status Ctx::offload(int32_t scope, ssdt_stream producer) {
   poll();
+  if (ssdt_status e = spill_status("offload")) return e;
   Ev *after = nullptr;
   for (size_t i = 0; i < recs.size(); ++i) {
     Rec &r = recs[i];
@@ -373,6 +547,7 @@ ssdt_status Ctx::offload(int32_t scope, ssdt_stream producer) {
 
 ssdt_status Ctx::prefetch(int32_t scope) {
   poll();
+  if (ssdt_status e = spill_status("prefetch")) return e;
   std::vector<size_t> todo;
   for (size_t i = recs.size(); i-- > 0;) {  // reverse of the order recorded in forward (Sec. 3.1)
     Rec &r = recs[i];
@@ -400,13 +575,8 @@ ssdt_status Ctx::prefetch(int32_t scope) {
     r.dev = slots[k];
     r.holds_ref = true;  // the reference alloc() gave now belongs to the record
     by_storage[r.dev] = todo[k];
-    drop(be.get(), r.load_ev);
-    r.load_ev = hold(be->copy(1, r.dev, (char *)be->pool() + r.pool_offset, r.bytes, nullptr));
-    if (!be->err.empty()) return fail(SSDT_E_HIP, "prefetch: %s", be->err.c_str());
-    r.state = SSDT_ST_LOADING;
-    r.load_waited = false;
-    ++st.loads;
-    st.bytes_loaded += r.bytes;
+    ssdt_status e = start_load(todo[k], "prefetch");
+    if (e != SSDT_OK) return e;
   }
   return SSDT_OK;
 }
@@ -430,14 +600,15 @@ ssdt_status Ctx::get(ssdt_tid tid, ssdt_stream consumer, void **out) {
     r.dev = p;
     r.holds_ref = true;
     by_storage[p] = it->second;
-    drop(be.get(), r.load_ev);
-    r.load_ev = hold(be->copy(1, p, (char *)be->pool() + r.pool_offset, r.bytes, nullptr));
-    if (!be->err.empty()) return fail(SSDT_E_HIP, "get: %s", be->err.c_str());
-    r.state = SSDT_ST_LOADING;
-    r.load_waited = false;
-    ++st.loads;
     ++st.demand_loads;
-    st.bytes_loaded += r.bytes;
+    ssdt_status e = start_load(it->second, "get");
+    if (e != SSDT_OK) return e;
+  }
+  if (r.read_pending) {  // spill mode: the host waits for the file, then the copy is enqueued
+    spill_in_pool((size_t)r.pool_offset, true);
+    ssdt_status e = spill_status("get");
+    if (e == SSDT_OK) e = issue_copy_in(it->second, "get");
+    if (e != SSDT_OK) return e;
   }
   if (r.load_ev) {
     if (!r.load_waited) {
@@ -466,7 +637,10 @@ ssdt_status Ctx::release(int32_t scope, ssdt_stream s) {
       continue;
     }
     if (r.holds_ref && r.dev) {
-      if (r.state == SSDT_ST_LOADING) {
+      if (r.state == SSDT_ST_LOADING && r.read_pending) {
+        r.read_pending = false;  // no copy was enqueued: nothing is in flight to the slot
+        unref(r.dev, nullptr, nullptr);
+      } else if (r.state == SSDT_ST_LOADING) {
         unref(r.dev, r.load_ev, be->queue_stream(1));
       } else {
         if (!ev) ev = hold(be->record(s, false));
@@ -499,7 +673,6 @@ ssdt_status ssdt_ctx_create(const ssdt_config *cfg, ssdt_ctx **out) {
   *out = nullptr;
   if (cfg->arena_bytes && (!cfg->arena_base || ((uintptr_t)cfg->arena_base % kAlignTensor) != 0)) return SSDT_E_INVAL;
   if (cfg->keep_last < 0 || cfg->min_offload_elems < 0) return SSDT_E_INVAL;
-  if (cfg->spill_path && cfg->spill_path[0]) return SSDT_E_UNSUPPORTED;
   std::string err;
   Backend *be = nullptr;
   if (cfg->backend == SSDT_BACKEND_HIP) be = make_hip_backend(cfg->pool_bytes, &err);
@@ -518,6 +691,13 @@ ssdt_status ssdt_ctx_create(const ssdt_config *cfg, ssdt_ctx **out) {
     b.size = cfg->arena_bytes / kAlignTensor * kAlignTensor;
     c->blocks[0] = b;
   }
+  if (cfg->spill_path && cfg->spill_path[0]) {
+    if (c->spill_open(cfg->spill_path) != SSDT_OK) {
+      fprintf(stderr, "ssdt_ctx_create: %s\n", c->last_error.c_str());
+      delete c;
+      return SSDT_E_IO;
+    }
+  }
   *out = c;
   return SSDT_OK;
 }
@@ -525,6 +705,7 @@ ssdt_status ssdt_ctx_create(const ssdt_config *cfg, ssdt_ctx **out) {
 ssdt_status ssdt_ctx_destroy(ssdt_ctx *ctx) {
   if (!ctx) return SSDT_E_INVAL;
   ctx->be->sync_io();
+  ctx->spill_close();
   delete ctx;
   return SSDT_OK;
 }
@@ -628,6 +809,14 @@ ssdt_status ssdt_pool_read(ssdt_ctx *c, size_t off, void *dst, size_t bytes) {
   if (!c || !dst) return SSDT_E_INVAL;
   if (off + bytes > c->cfg.pool_bytes) return c->fail(SSDT_E_INVAL, "pool_read: range outside the pool");
   c->be->sync_io();
+  if (c->spill) {  // the file is the store: finish the pending writes and read it
+    c->poll();
+    c->spill_drain();
+    if (ssdt_status e = c->spill_status("pool_read")) return e;
+    std::string err;
+    if (!rw_all(c->spill->fd, (char *)dst, bytes, off, false, &err)) return c->fail(SSDT_E_IO, "pool_read: %s", err.c_str());
+    return SSDT_OK;
+  }
   memcpy(dst, (char *)c->be->pool() + off, bytes);
   return SSDT_OK;
 }
@@ -670,6 +859,20 @@ ssdt_status ssdt_sync_io(ssdt_ctx *c) {
   if (!c) return SSDT_E_INVAL;
   c->be->sync_io();
   c->poll();
+  if (c->spill) {
+    c->spill_drain();
+    c->poll();
+    return c->spill_status("sync_io");
+  }
+  return SSDT_OK;
+}
+
+ssdt_status ssdt_spill_stats(ssdt_ctx *c, uint64_t *bytes_written, uint64_t *bytes_read) {
+  if (!c) return SSDT_E_INVAL;
+  if (!c->spill) return c->fail(SSDT_E_STATE, "spill_stats: the context has no spill file");
+  std::lock_guard<std::mutex> g(c->spill->mu);
+  if (bytes_written) *bytes_written = c->spill->bytes_written;
+  if (bytes_read) *bytes_read = c->spill->bytes_read;
   return SSDT_OK;
 }
 

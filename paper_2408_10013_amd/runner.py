@@ -78,7 +78,7 @@ class Stack:
     """A stack of layers on one GPU with its tensor-cache context."""
 
     def __init__(self, layers: List[Layer], arena_bytes: int, pool_bytes: int, device="cuda:0", keep_last=1,
-                 min_offload_elems=1 << 20, budget_bytes=-1, measure_waits=0):
+                 min_offload_elems=1 << 20, budget_bytes=-1, measure_waits=0, spill_path=None):
         self.layers = layers
         self.dev = torch.device(device)
         self.dtype = layers[0].dtype
@@ -89,7 +89,7 @@ class Stack:
         self.ctx = sb.ssdt_ctx_create(backend=sb.BACKEND_HIP, keep_last=keep_last, min_offload_elems=min_offload_elems,
                                       budget_bytes=budget_bytes, arena_base=self.arena_base,
                                       arena_bytes=arena_bytes - (self.arena_base - base), pool_bytes=pool_bytes,
-                                      measure_waits=measure_waits)
+                                      measure_waits=measure_waits, spill_path=spill_path)
         fb = bb = 0
         for l in layers:
             f, b = sb.ssdt_layer_workspace(l.desc)

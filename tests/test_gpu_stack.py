@@ -104,6 +104,33 @@ def test_gpt_stack_parity_bookkeeping_and_transparency(dtype):
     assert results["off"][6]["offloaded"] == 0 and results["on"][6]["released"] == 4 * 13
 
 
+def test_spill_file_tier_is_transparent(tmp_path):
+    """With a spill file every reloaded tensor comes from the file (its pool bytes are overwritten
+    after the write): outputs and gradients must still equal those without one, bit for bit."""
+    dtype = "bf16"
+    mk = lambda: [runner.Layer("gpt_preln", dtype, B=2, S=128, H=128, A=2, F=256, act="gelu", norm="layernorm",
+                               mask="causal", has_bias=True, eps=1e-5) for _ in range(4)]
+    cases = [hp.make_layer_case(l, 300 + i, bias_std=0.05) for i, l in enumerate(mk())]
+    x = runner.to_device(cases[0]["x"], dtype, DEV)
+    dy = runner.to_device(cases[0]["dy"], dtype, DEV)
+    per = runner.saved_bytes_per_layer(mk()[0])
+    res = {}
+    for name, path in (("pool", None), ("file", str(tmp_path / "spill.bin"))):
+        ls = mk()
+        st = build(ls, cases, 3 * per, 5 * per, keep_last=0, min_offload_elems=0, budget_bytes=-1, spill_path=path)
+        res[name] = run_gpu(st, ls, x, dy)
+        if path:
+            sb.ssdt_sync_io(st.ctx)
+            w, r = sb.ssdt_spill_stats(st.ctx)
+            fin = res[name][6]
+            assert fin["loads"] > 0 and 0 < r <= fin["bytes_loaded"] and w >= r
+        st.close()
+    assert torch.equal(res["pool"][0], res["file"][0]) and torch.equal(res["pool"][1], res["file"][1])
+    for ga, gb in zip(res["pool"][3], res["file"][3]):
+        for k in ga:
+            assert torch.equal(ga[k], gb[k]), k
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_t5_encoder_decoder_stack(dtype):
     B, S, Se, H, A, F = 2, 128, 256, 128, 2, 256

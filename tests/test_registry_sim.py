@@ -324,5 +324,79 @@ def test_error_paths():
         sb.ssdt_ctx_create(backend=sb.BACKEND_SIM, arena_base=ar.base + 8, arena_bytes=1024)
     assert e.value.status == sb.E_INVAL
     with pytest.raises(sb.SsdtError) as e:
-        sb.ssdt_ctx_create(backend=sb.BACKEND_SIM, spill_path="/tmp/x")
-    assert e.value.status == sb.E_UNSUPPORTED
+        sb.ssdt_ctx_create(backend=sb.BACKEND_SIM, spill_path="/nonexistent-dir/spill.bin")
+    assert e.value.status == sb.E_IO
+
+
+def _spill_step(ctx, ar, fill):
+    """Two layers of three 1 KiB tensors each; returns {name: (tid, pool_offset)}."""
+    sb.ssdt_step_begin(ctx, 2)
+    out = {}
+    for l, names in ((0, "abc"), (1, "def")):
+        sb.ssdt_scope_begin(ctx, l)
+        for n in names:
+            p = sb.ssdt_arena_alloc(ctx, 1024)
+            ar.view(p, 1024)[:] = fill[n]
+            out[n] = sb.ssdt_save(ctx, p, 1024, 0, [256], sb.F32)
+            sb.ssdt_arena_free(ctx, p)
+        sb.ssdt_scope_end(ctx, l)
+        sb.ssdt_offload(ctx, l)
+    rec = {r["tid"]: r for r in records(ctx)}
+    return {n: (t, rec[t]["pool_offset"]) for n, t in out.items()}
+
+
+def test_spill_file_is_the_store_and_reloads_are_bit_identical(tmp_path):
+    path = str(tmp_path / "spill.bin")
+    ctx, ar = make(arena_bytes=1 << 16, spill_path=path)
+    for step in range(2):                               # the second step reuses the same file offsets
+        fill = {n: (ord(n) + 7 * step) & 0xFF for n in "abcdef"}
+        t = _spill_step(ctx, ar, fill)
+        assert sb.ssdt_sim_complete(ctx, 0, 4) == 4     # a..d are off the device, e and f still on their way
+        sb.ssdt_prefetch(ctx, 1)                        # f, e forwarded; d comes back from the file
+        sb.ssdt_prefetch(ctx, 0)
+        s = sb.ssdt_get_stats(ctx)
+        assert s["forwarded"] == 2 and s["loads"] == 4
+        for n in "fedcba":
+            p = sb.ssdt_get(ctx, t[n][0])
+            assert bytes(ar.view(p, 1024)) == bytes([fill[n]]) * 1024, n
+        sb.ssdt_sync_io(ctx)
+        w, r = sb.ssdt_spill_stats(ctx)
+        assert (w, r) == (4096 * (step + 1), 4096 * (step + 1))   # forwarded tensors never reach the file
+        with open(path, "rb") as f:
+            blob = f.read()
+        for n in "abcd":
+            off = t[n][1]
+            assert blob[off:off + 1024] == bytes([fill[n]]) * 1024
+            assert sb.ssdt_pool_read(ctx, off, 1024) == bytes([fill[n]]) * 1024
+        sb.ssdt_release(ctx, 1)
+        sb.ssdt_release(ctx, 0)
+        assert sb.ssdt_get_stats(ctx)["arena_in_use"] == 0
+    sb.ssdt_ctx_destroy(ctx)
+
+
+def test_spill_release_before_the_read_was_used_and_demand_load(tmp_path):
+    ctx, ar = make(arena_bytes=1 << 16, spill_path=str(tmp_path / "s.bin"))
+    fill = {n: ord(n) for n in "abcdef"}
+    t = _spill_step(ctx, ar, fill)
+    sb.ssdt_sync_io(ctx)                                # everything stored and written
+    p = sb.ssdt_get(ctx, t["e"][0])                     # nobody prefetched it: demand load through the file
+    assert bytes(ar.view(p, 1024)) == b"e" * 1024
+    assert sb.ssdt_get_stats(ctx)["demand_loads"] == 1
+    sb.ssdt_prefetch(ctx, 0)                            # reads requested ...
+    sb.ssdt_release(ctx, 0)                             # ... and the scope released before any copy was issued
+    sb.ssdt_release(ctx, 1)
+    assert sb.ssdt_get_stats(ctx)["arena_in_use"] == 0
+    sb.ssdt_step_begin(ctx, 2)
+    sb.ssdt_ctx_destroy(ctx)
+
+
+def test_spill_write_failure_is_reported():
+    ctx, ar = make(arena_bytes=1 << 16, spill_path="/dev/full")    # every write fails with ENOSPC
+    t = _spill_step(ctx, ar, {n: ord(n) for n in "abcdef"})
+    with pytest.raises(sb.SsdtError) as e:
+        sb.ssdt_sync_io(ctx)
+    assert e.value.status == sb.E_IO and "spill write" in str(e.value)
+    with pytest.raises(sb.SsdtError) as e:
+        sb.ssdt_prefetch(ctx, 1)
+    assert e.value.status == sb.E_IO
+    sb.ssdt_ctx_destroy(ctx)
