@@ -583,9 +583,45 @@ __global__ __launch_bounds__(256) void transpose_k(const U *in, long ldi, U *out
     if (c0 + c < cols && r0 + tx < rows) out[(long)(c0 + c) * ldo + r0 + tx] = tile[tx][c];
 }
 
+// 16-bit elements, extents multiples of 64, 16-byte aligned rows: each wavefront moves a 64x64 tile with
+// 16-byte accesses only and no LDS.  Lane (rb, cb) = (lane / 8, lane % 8) reads the 8x8 block at rows
+// 8 rb.., columns 8 cb.. (eight lanes cover one 128-byte line of each row), transposes it in registers and
+// writes it as rows 8 cb.., columns 8 rb.. of the output (again eight lanes per 128-byte line).
+__global__ __launch_bounds__(256) void transpose16_k(const uint16_t *in, long ldi, uint16_t *out, long ldo, int rows, int cols) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r0 = (blockIdx.y * 2 + (wave >> 1)) * 64, c0 = (blockIdx.x * 2 + (wave & 1)) * 64;
+  if (r0 >= rows || c0 >= cols) return;
+  const int rb = lane >> 3, cb = lane & 7;
+  const uint16_t *src = in + (long)(r0 + rb * 8) * ldi + c0 + cb * 8;
+  uint32_t v[8][4];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const uint4 q = *(const uint4 *)(src + i * ldi);
+    v[i][0] = q.x; v[i][1] = q.y; v[i][2] = q.z; v[i][3] = q.w;
+  }
+  uint16_t *dst = out + (long)(c0 + cb * 8) * ldo + r0 + rb * 8;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {  // output row j of the block = column j of the input block
+    uint32_t o[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const uint32_t a = v[2 * k][j >> 1], b = v[2 * k + 1][j >> 1];
+      o[k] = (j & 1) ? ((a >> 16) | (b & 0xffff0000u)) : ((a & 0xffffu) | (b << 16));
+    }
+    *(uint4 *)(dst + j * ldo) = make_uint4(o[0], o[1], o[2], o[3]);
+  }
+}
+
 hipError_t transpose(const void *in, long ldi, void *out, long ldo, int rows, int cols, int dtype, hipStream_t s) {
   dim3 grid((cols + 63) / 64, (rows + 63) / 64);
   prof::Scope ps(prof::TRANSPOSE, 0, 2.0 * rows * cols * (dtype == SSDT_F32 ? 4 : 2), s);
+  if (dtype != SSDT_F32 && rows % 64 == 0 && cols % 64 == 0 && ldi % 8 == 0 && ldo % 8 == 0 &&
+      ((uintptr_t)in | (uintptr_t)out) % 16 == 0) {
+    hipLaunchKernelGGL(transpose16_k, dim3((cols + 127) / 128, (rows + 127) / 128), dim3(256), 0, s, (const uint16_t *)in, ldi,
+                       (uint16_t *)out, ldo, rows, cols);
+    SSDT_LAUNCH_CHECK();
+    return hipSuccess;
+  }
   if (dtype == SSDT_F32)
     hipLaunchKernelGGL(transpose_k<uint32_t>, grid, dim3(256), 0, s, (const uint32_t *)in, ldi, (uint32_t *)out, ldo, rows, cols);
   else

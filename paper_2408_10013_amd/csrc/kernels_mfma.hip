@@ -239,36 +239,47 @@ __global__ __launch_bounds__(512) void gemm_nt256_k(NtP p) {
   const unsigned ob2 = brow + ((4 + half) ^ sw) * 16, ob3 = brow + ((6 + half) ^ sw) * 16;
   v4i_t pa0, pa1, pa2, pa3, pb0, pb1, qa0, qa1, qa2, qa3, qb0, qb1;
 
-  // The next stage's loads are spread over the four sub-steps (two per sub-step): issued in one burst they
-  // would sit in the address pipeline for ~1000 cycles and hold back the MFMAs queued behind them.
+  // Software pipeline over the 64-wide stages.  A stage's four 16-wide sub-steps alternate between the
+  // register sets P and Q.  The wait for the next stage (its loads have landed, everyone is done reading
+  // the current one) sits BEFORE the last sub-step's MFMAs, once this wavefront holds all operands of the
+  // current stage: the first fragments of the next stage are then read under those MFMAs instead of under
+  // an idle matrix pipe.  The loads of the stage after next go out in small groups (1, 2, 1 pairs) at the
+  // barrier and in the first two sub-steps: a burst of all eight holds back the MFMAs queued behind it,
+  // a later issue leaves them too little time before the wait.
+  __builtin_amdgcn_s_waitcnt(0xF70);
+  __builtin_amdgcn_s_barrier();
+  if (nk > 1) SSDT_ISSUE2(1, 0);
+  SSDT_READ6(pa0, pa1, pa2, pa3, pb0, pb1, oa0, ob0);
   for (int kt = 0; kt < nk; ++kt) {
-    __builtin_amdgcn_s_waitcnt(0xF70);  // vmcnt(0): this wavefront's part of stage kt has landed
-    __builtin_amdgcn_s_barrier();       // so has everyone's; and everyone is done reading stage kt-1
-    const unsigned so = (kt & 1) * kStage2 * 2;
-    const bool more = kt + 1 < nk;
-    SSDT_READ6(pa0, pa1, pa2, pa3, pb0, pb1, oa0 + so, ob0 + so);
+    const unsigned so = (kt & 1) * kStage2 * 2, so1 = ((kt + 1) & 1) * kStage2 * 2;
+    const bool more = kt + 1 < nk, more2 = kt + 2 < nk;
     SSDT_READ6(qa0, qa1, qa2, qa3, qb0, qb1, oa1 + so, ob1 + so);
     SSDT_WAIT6(6, pa0, pa1, pa2, pa3, pb0, pb1);
-    if (more) SSDT_ISSUE2(kt + 1, 0);
+    if (more) { SSDT_ISSUE2(kt + 1, 1); SSDT_ISSUE2(kt + 1, 2); }
     __builtin_amdgcn_sched_barrier(0);
     SSDT_MFMA8(pa0, pa1, pa2, pa3, pb0, pb1);
     __builtin_amdgcn_sched_barrier(0);
     SSDT_READ6(pa0, pa1, pa2, pa3, pb0, pb1, oa2 + so, ob2 + so);
     SSDT_WAIT6(6, qa0, qa1, qa2, qa3, qb0, qb1);
-    if (more) SSDT_ISSUE2(kt + 1, 1);
+    if (more) SSDT_ISSUE2(kt + 1, 3);
     __builtin_amdgcn_sched_barrier(0);
     SSDT_MFMA8(qa0, qa1, qa2, qa3, qb0, qb1);
     __builtin_amdgcn_sched_barrier(0);
     SSDT_READ6(qa0, qa1, qa2, qa3, qb0, qb1, oa3 + so, ob3 + so);
     SSDT_WAIT6(6, pa0, pa1, pa2, pa3, pb0, pb1);
-    if (more) SSDT_ISSUE2(kt + 1, 2);
     __builtin_amdgcn_sched_barrier(0);
     SSDT_MFMA8(pa0, pa1, pa2, pa3, pb0, pb1);
     __builtin_amdgcn_sched_barrier(0);
-    SSDT_WAIT6(0, qa0, qa1, qa2, qa3, qb0, qb1);
-    if (more) SSDT_ISSUE2(kt + 1, 3);
+    SSDT_WAIT6(0, qa0, qa1, qa2, qa3, qb0, qb1);  // this wavefront now holds everything it needs of stage kt
+    if (more) {
+      __builtin_amdgcn_s_waitcnt(0xF70);  // vmcnt(0): its part of stage kt+1 has landed
+      __builtin_amdgcn_s_barrier();       // so has everyone's; and everyone is done reading stage kt
+      if (more2) SSDT_ISSUE2(kt + 2, 0);
+      SSDT_READ6(pa0, pa1, pa2, pa3, pb0, pb1, oa0 + so1, ob0 + so1);
+    }
     __builtin_amdgcn_sched_barrier(0);
     SSDT_MFMA8(qa0, qa1, qa2, qa3, qb0, qb1);
+    __builtin_amdgcn_sched_barrier(0);
   }
 #undef SSDT_ISSUE2
 #undef SSDT_ISSUE
