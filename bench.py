@@ -6,6 +6,7 @@ synthetic tensors (inputs resident in HBM), including every offload, prefetch an
 Three modes are timed back to back with the same context and arena:
   off     offload amount 0: every saved tensor stays on the device
   all     every saved tensor of every layer but the last is offloaded and prefetched back
+  recompute  nothing offloaded, every layer re-run inside its backward (only with --modes ...,recompute)
   budget  the offload amount is set from the measured link rate so that the I/O hides
           behind compute (the paper's adaptive offload amount, Sec. 3.1); the headline value
 The JSON line printed at the end carries the headline (budget mode), the other two modes,
@@ -152,11 +153,13 @@ def main():
         flops = stack_flops(layers, kv_len.cpu().numpy() if kv_len is not None else None)
         setup = {}
 
-        def run_mode(name, budget, arena_bytes, pool_bytes, profile=False):
+        def run_mode(name, budget, arena_bytes, pool_bytes, profile=False, distance=1, recompute=False):
             """One context per mode: the arena size is what bounds the activation memory of that mode."""
             t0 = time.perf_counter()
             st = runner.Stack(layers, arena_bytes, pool_bytes, "cuda:0", keep_last=1, min_offload_elems=1 << 20,
                               budget_bytes=budget, measure_waits=1)
+            st.prefetch_distance = distance
+            st.recompute = recompute
             st.register_weights()
             setup[name] = time.perf_counter() - t0
 
@@ -198,14 +201,27 @@ def main():
             # three layers' worth of arena: the layer computing, the one being stored / loaded, and slack
             modes["all"], _ = run_mode("all", -1, 3 * max(per_layer) + (64 << 20), runner.pool_bytes_needed(layers))
         if "budget" in want:
-            # offload amount the link can drain while the forward runs (Sec. 3.1: the amount is set from the amount
-            # of computation, the activation size, the GPU throughput and the I/O bandwidth); the arena shrinks by
-            # what is expected to have left the device by the end of the forward pass
-            t_fwd = modes["off"]["ms_per_step"] * 1e-3 / 3.0
-            budget = int(min(0.85 * link["d2h"] * 1e9 * t_fwd, sum(per_layer[:-1])))
+            # The offload amount comes from the planner (Sec. 3.1: it is set from the amount of computation, the
+            # activation sizes, the GPU throughput and the I/O bandwidth): per-layer times are the layers' FLOP
+            # shares of the measured step without offload, the rates are the measured link rates.  The arena
+            # shrinks by what is expected to have left the device by the end of the forward pass.
+            t_off = modes["off"]["ms_per_step"] * 1e-3
+            lf = [stack_flops([l], kv_len.cpu().numpy() if kv_len is not None else None) for l in layers]
+            fwd_s = [t_off * f / sum(lf) / 3.0 for f in lf]
+            plan = sb.ssdt_plan(per_layer, fwd_s, [2.0 * t for t in fwd_s], link["d2h"] * 1e9, link["h2d"] * 1e9,
+                                safety=0.85, keep_last=1)
+            budget = plan["budget_bytes"]
             arena = modes["off"]["arena_peak_bytes"] + (256 << 20) + max(per_layer) // 4 - int(0.75 * budget)
-            modes["budget"], prof = run_mode("budget", budget, arena, budget + (256 << 20), profile=True)
+            modes["budget"], prof = run_mode("budget", budget, arena, budget + (256 << 20), profile=True,
+                                             distance=max(1, plan["prefetch_distance"]))
+            modes["budget"]["plan"] = plan
             modes["budget"]["budget_bytes"] = budget
+        if "recompute" in want:
+            # layerwise full recomputation, nothing offloaded: the third arm of the comparison in Sec. 4.3.  Its
+            # rate counts the algorithmic FLOPs only (the repeated forward is overhead, as in the paper's "model
+            # throughput").
+            modes["recompute"], _ = run_mode("recompute", 0, sum(l.T * l.H * (4 if l.dtype == "f32" else 2) for l in layers) + 2 * max(per_layer)
+                                             + (256 << 20), 0, recompute=True)
         for k, m in modes.items():
             m["exposed_io_pct"] = max(0.0, (m["ms_per_step"] - modes["off"]["ms_per_step"]) / m["ms_per_step"] * 100.0)
             m["arena_peak_vs_off"] = m["arena_peak_bytes"] / max(1, modes["off"]["arena_peak_bytes"])

@@ -139,6 +139,40 @@ ssdt_status ssdt_step_begin(ssdt_ctx *ctx, int32_t num_layers);
 /* Changes the per-step offload amount (same meaning as ssdt_config.budget_bytes). */
 ssdt_status ssdt_set_budget(ssdt_ctx *ctx, int64_t budget_bytes);
 
+/* ---- offload amount ---------------------------------------------------------------------- */
+
+/* Inputs of ssdt_plan: per-layer figures of one training step, forward order, all HOST memory. */
+typedef struct ssdt_plan_in {
+  int32_t num_layers;
+  int32_t keep_last;            /* trailing layers that are never offloaded (Sec. 3.3.2) */
+  const uint64_t *layer_bytes;  /* [num_layers] bytes each layer saves that can be offloaded */
+  const double *fwd_s;          /* [num_layers] forward time of each layer, seconds */
+  const double *bwd_s;          /* [num_layers] backward time of each layer, seconds */
+  double store_Bps;             /* device -> pool (or file) rate, bytes / s */
+  double load_Bps;              /* pool (or file) -> device rate, bytes / s */
+  double safety;                /* in (0, 1]: share of both rates the plan may count on */
+} ssdt_plan_in;
+
+typedef struct ssdt_plan_out {
+  int64_t budget_bytes;         /* value for ssdt_config.budget_bytes / ssdt_set_budget */
+  int32_t layers;               /* leading layers entirely within the amount */
+  int32_t prefetch_distance;    /* smallest d such that loading layer l when the backward of layer l+d starts
+                                   hides every load; 0 if nothing is offloaded */
+  uint64_t partial_bytes;       /* bytes of layer `layers` that are also within the amount */
+  double store_done_s;          /* predicted end of the last store, from the start of the step */
+  double fwd_total_s;
+} ssdt_plan_out;
+
+/* Sets the offload amount of a step from the amount of computation, the activation sizes and the
+ * transfer rates (Sec. 3.1, workflow; Sec. 3.2, first condition of the pack hook).  Stores form one
+ * queue in forward order, a layer's tensors being available when its forward ends; a byte is counted
+ * only if it leaves the device before the forward pass ends, where the activation peak is reached.
+ * Loads form one queue in reverse order and each must be complete when its layer's backward starts;
+ * if no prefetch distance achieves that the amount is cut back, the partial layer first.  Pure host
+ * arithmetic: needs no context and no GPU.  SSDT_E_INVAL for null pointers, num_layers <= 0,
+ * negative times or keep_last, rates <= 0, safety outside (0, 1]. */
+ssdt_status ssdt_plan(const ssdt_plan_in *in, ssdt_plan_out *out);
+
 /* ---- device arena ----------------------------------------------------------------------- */
 
 /* Sub-allocates `bytes` (rounded up to 256) from the arena for use on `stream`.  Memory whose
@@ -240,6 +274,11 @@ typedef struct ssdt_layer_desc {
   int32_t B, S, S_kv, H, A, F; /* micro-batch, (query) length, encoder length (T5_DEC), hidden, heads, FFN */
   float eps;                   /* norm epsilon */
   float softmax_scale;         /* 0 = 1/sqrt(H/A) */
+  int32_t checkpoint;          /* nonzero: ssdt_layer_fwd registers only the layer's inputs (x, enc_out) for
+                                  backward and frees every intermediate; the caller recomputes the layer
+                                  inside its backward scope before ssdt_layer_bwd (layerwise full
+                                  recomputation, the comparison arm of Sec. 4.3) */
+  int32_t reserved;
 } ssdt_layer_desc;
 
 /* DEVICE pointers, element type = desc.dtype.  Matrices are row-major [in, out] (y = x W + b);

@@ -19,7 +19,9 @@ Rules, in the order the pack hook applies them to one save call:
   4. the current scope (top of the forward scope stack) is added to the record's scopes
   5. the storage is KEPT when its layer is among the last `keep_last` layers of the
      step, or when `offloaded_so_far + bytes > budget_bytes`, or when its pack would
-     overflow the host pool; otherwise it is OFFLOADED and `offloaded_so_far += bytes`
+     overflow the host pool, or when the save happens inside backward propagation (a
+     checkpointed module recomputing its activations: second condition of the pack
+     hook's keep test, Sec. 3.2); otherwise it is OFFLOADED and `offloaded_so_far += bytes`
 
 Host-pool layout: the OFFLOADED storages of one layer (the scope at the bottom of the
 scope stack) form a pack, in first-save order, each starting at the next multiple of
@@ -85,6 +87,7 @@ class RegistryOracle:
         self.pack_cursor: Dict[int, int] = {}     # layer -> bytes used inside its pack
         self.pack_base: Dict[int, int] = {}       # layer -> pool offset of its pack
         self.pool_cursor = 0
+        self.in_backward = 0                      # depth of open backward scopes
 
     # -- events ------------------------------------------------------------------------
     def register_weight(self, storage) -> None:
@@ -97,6 +100,13 @@ class RegistryOracle:
             self.pack_base[scope] = self.pool_cursor
             self.pack_cursor[scope] = 0
         self.stack.append(scope)
+
+    def backward_begin(self) -> None:
+        self.in_backward += 1
+
+    def backward_end(self) -> None:
+        assert self.in_backward > 0
+        self.in_backward -= 1
 
     def scope_end(self, scope: int) -> None:
         assert self.stack and self.stack[-1] == scope
@@ -133,7 +143,7 @@ class RegistryOracle:
         off = _up(self.pack_cursor[layer], ALIGN_TENSOR)
         nomem = (self.pool_bytes is not None and
                  _up(self.pack_base[layer] + off + storage_bytes, ALIGN_PACK) > self.pool_bytes)
-        if in_last or over or nomem:
+        if in_last or over or nomem or self.in_backward > 0:
             c.kept += 1
             c.bytes_kept += storage_bytes
             return rec.stamp

@@ -64,6 +64,17 @@ class ssdt_record(C.Structure):
                 ("pool_offset", C.c_int64), ("device_ptr", C.c_void_p)]
 
 
+class ssdt_plan_in(C.Structure):
+    _fields_ = [("num_layers", C.c_int32), ("keep_last", C.c_int32), ("layer_bytes", C.POINTER(C.c_uint64)),
+                ("fwd_s", C.POINTER(C.c_double)), ("bwd_s", C.POINTER(C.c_double)), ("store_Bps", C.c_double),
+                ("load_Bps", C.c_double), ("safety", C.c_double)]
+
+
+class ssdt_plan_out(C.Structure):
+    _fields_ = [("budget_bytes", C.c_int64), ("layers", C.c_int32), ("prefetch_distance", C.c_int32),
+                ("partial_bytes", C.c_uint64), ("store_done_s", C.c_double), ("fwd_total_s", C.c_double)]
+
+
 class ssdt_kernel_time(C.Structure):
     _fields_ = [("name", C.c_char * 48), ("launches", C.c_uint64), ("ms", C.c_double), ("flops", C.c_double),
                 ("bytes", C.c_double)]
@@ -71,7 +82,8 @@ class ssdt_kernel_time(C.Structure):
 
 class ssdt_layer_desc(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("arch", "dtype", "act", "norm", "mask", "has_bias", "B", "S", "S_kv", "H",
-                                         "A", "F")] + [("eps", C.c_float), ("softmax_scale", C.c_float)]
+                                         "A", "F")] + [("eps", C.c_float), ("softmax_scale", C.c_float),
+                                                        ("checkpoint", C.c_int32), ("reserved", C.c_int32)]
 
 
 class ssdt_layer_weights(C.Structure):
@@ -112,6 +124,7 @@ _PROTOS = {
     "ssdt_pool_read": (C.c_int32, [C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t]),
     "ssdt_sim_complete": (C.c_int32, [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_int32)]),
     "ssdt_sync_io": (C.c_int32, [C.c_void_p]),
+    "ssdt_plan": (C.c_int32, [C.POINTER(ssdt_plan_in), C.POINTER(ssdt_plan_out)]),
     "ssdt_spill_stats": (C.c_int32, [C.c_void_p, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)]),
     "ssdt_profile": (C.c_int32, [C.c_void_p, C.c_int32]),
     "ssdt_profile_read": (C.c_int32, [C.c_void_p, C.POINTER(ssdt_kernel_time), C.c_uint32, C.POINTER(C.c_uint32)]),
@@ -261,6 +274,19 @@ def ssdt_sync_io(ctx):
     _check(ctx, lib().ssdt_sync_io(ctx), "ssdt_sync_io")
 
 
+def ssdt_plan(layer_bytes, fwd_s, bwd_s, store_Bps, load_Bps, safety=1.0, keep_last=1) -> dict:
+    n = len(layer_bytes)
+    if not (len(fwd_s) == len(bwd_s) == n):
+        raise ValueError("ssdt_plan: per-layer arrays differ in length")
+    lb = (C.c_uint64 * max(n, 1))(*[int(b) for b in layer_bytes])
+    fw = (C.c_double * max(n, 1))(*[float(t) for t in fwd_s])
+    bw = (C.c_double * max(n, 1))(*[float(t) for t in bwd_s])
+    pin = ssdt_plan_in(n, keep_last, lb, fw, bw, store_Bps, load_Bps, safety)
+    out = ssdt_plan_out()
+    _check(None, lib().ssdt_plan(C.byref(pin), C.byref(out)), "ssdt_plan")
+    return {f: getattr(out, f) for f, _ in ssdt_plan_out._fields_}
+
+
 def ssdt_spill_stats(ctx):
     w, r = C.c_uint64(0), C.c_uint64(0)
     _check(ctx, lib().ssdt_spill_stats(ctx, C.byref(w), C.byref(r)), "ssdt_spill_stats")
@@ -280,9 +306,9 @@ def ssdt_profile_read(ctx) -> list:
 
 
 def make_desc(arch="gpt_preln", dtype="f32", act="gelu", norm="layernorm", mask="causal", has_bias=True, B=1, S=1,
-              S_kv=0, H=1, A=1, F=1, eps=1e-5, softmax_scale=0.0) -> ssdt_layer_desc:
+              S_kv=0, H=1, A=1, F=1, eps=1e-5, softmax_scale=0.0, checkpoint=False) -> ssdt_layer_desc:
     return ssdt_layer_desc(ARCH[arch], DTYPE[dtype], ACT[act], NORM[norm], MASK[mask], int(bool(has_bias)), B, S, S_kv,
-                           H, A, F, eps, softmax_scale)
+                           H, A, F, eps, softmax_scale, int(bool(checkpoint)), 0)
 
 
 def make_weights(ptrs: dict) -> ssdt_layer_weights:

@@ -82,6 +82,15 @@ struct Rec {
   Ev *store_ev = nullptr, *load_ev = nullptr;
 };
 
+// events are shared by reference count: hold() on taking one, drop() when done with it
+static inline Ev *hold(Ev *e) {
+  if (e) ++e->refs;
+  return e;
+}
+static inline void drop(Backend *be, Ev *e) {
+  if (e && --e->refs <= 0) be->recycle(e);
+}
+
 struct WaitPair { Ev *a, *b; int kind; };
 
 // Spill file: the tier behind the pinned pool (Sec. 3.1 names an SSD offloader beside the CPU

@@ -146,7 +146,9 @@ ssdt_status ssdt_layer_fwd(ssdt_ctx *ctx, const ssdt_layer_desc *desc, const ssd
     return SSDT_OK;
   };
   // the pack hook on a whole storage / on a [rows, cols] view at a byte offset into it
+  const bool ckpt = desc->checkpoint != 0;  // only the layer's inputs are kept for backward
   auto save = [&](int idx, const void *base, size_t sbytes, size_t off, int64_t rows, int64_t cols, int sdt) -> ssdt_status {
+    if (ckpt && base != x && base != enc_out) return SSDT_OK;
     int64_t shp[2] = {rows, cols};
     ssdt_tid tid = 0;
     ssdt_status r = ctx->save(base, sbytes, off, shp, 2, sdt, &tid);
@@ -290,8 +292,19 @@ ssdt_status ssdt_layer_fwd(ssdt_ctx *ctx, const ssdt_layer_desc *desc, const ssd
   }
   // every block allocated here is now referenced by the registry; drop this call's references,
   // except y, which the caller owns
-  for (void *p : mine)
-    if (p != y) ctx->unref(p, nullptr, nullptr);
+  if (ckpt) {
+    // nothing but the inputs was registered: the intermediates return to the arena once the kernels
+    // enqueued above have run, and the caller gets no pointers to them
+    Ev *done = hold(ctx->be->record(stream, false));
+    for (void *p : mine)
+      if (p != y) ctx->unref(p, done, stream);
+    drop(ctx->be.get(), done);
+    for (int i = 0; i < SSDT_SV_COUNT; ++i)
+      if (saved->e[i].ptr != x && saved->e[i].ptr != enc_out) saved->e[i] = ssdt_saved_entry{};
+  } else {
+    for (void *p : mine)
+      if (p != y) ctx->unref(p, nullptr, nullptr);
+  }
   mine.clear();
   *y_out = y;
   return ctx->scope_end(scope, SSDT_FWD);

@@ -26,13 +26,6 @@ ssdt_status Ctx::fail(ssdt_status code, const char *fmt, ...) {
   return code;
 }
 
-static inline Ev *hold(Ev *e) {
-  if (e) ++e->refs;
-  return e;
-}
-static inline void drop(Backend *be, Ev *e) {
-  if (e && --e->refs <= 0) be->recycle(e);
-}
 
 // ---------------------------------------------------------------------------------------
 // arena: first-fit by address over a map of blocks; blocks are reference counted (the
@@ -502,7 +495,8 @@ ssdt_status Ctx::save(const void *base, size_t sbytes, size_t view_off, const in
     bool over = cfg.budget_bytes >= 0 && st.bytes_offloaded + sbytes > (uint64_t)cfg.budget_bytes;
     size_t off = up(pack_cursor[layer], kAlignTensor);
     bool nomem = up(pack_base[layer] + off + sbytes, kAlignPack) > cfg.pool_bytes;
-    if (in_last || over || nomem || !arena) {
+    const bool recomputing = !bwd_open.empty();  // a checkpointed module re-running its forward (Sec. 3.2)
+    if (in_last || over || nomem || !arena || recomputing) {
       r.cls = SSDT_CLS_KEPT;
       ++st.kept;
       st.bytes_kept += sbytes;

@@ -58,6 +58,8 @@ class Layer:
         self.act, self.norm, self.mask, self.has_bias, self.eps = act, norm, mask, has_bias, eps
         self.desc = sb.make_desc(arch=arch, dtype=dtype, act=act, norm=norm, mask=mask, has_bias=has_bias, B=B, S=S,
                                  S_kv=S_kv, H=H, A=A, F=F, eps=eps)
+        self.desc_ckpt = sb.make_desc(arch=arch, dtype=dtype, act=act, norm=norm, mask=mask, has_bias=has_bias, B=B,
+                                      S=S, S_kv=S_kv, H=H, A=A, F=F, eps=eps, checkpoint=True)
         self.shapes = weight_shapes(arch, norm, has_bias, H, F)
         self.w: Dict[str, torch.Tensor] = {}
         self.g: Dict[str, torch.Tensor] = {}
@@ -99,6 +101,9 @@ class Stack:
         self.ws_ptr = (self.ws.data_ptr() + 255) // 256 * 256
         self.stream = torch.cuda.current_stream(self.dev).cuda_stream
         self.prefetch_distance = 1
+        # layerwise full recomputation (the comparison arm of Sec. 4.3): forward registers only each layer's
+        # input, backward re-runs the layer's forward inside its backward scope
+        self.recompute = False
 
     def close(self):
         if self.ctx:
@@ -143,8 +148,8 @@ class Stack:
             v.copy_(inp)
             for i in range(lo, hi):
                 l = self.layers[i]
-                y, l.saved = sb.ssdt_layer_fwd(ctx, l.desc, l.wstruct, i, p, enc, kvp, self.ws_ptr, self.ws_bytes,
-                                               self.stream)
+                y, l.saved = sb.ssdt_layer_fwd(ctx, l.desc_ckpt if self.recompute else l.desc, l.wstruct, i, p, enc, kvp,
+                                               self.ws_ptr, self.ws_bytes, self.stream)
                 if offload:
                     sb.ssdt_offload(ctx, i, self.stream)
                 sb.ssdt_arena_free(ctx, p, self.stream)   # drop the caller's reference on the layer input
@@ -183,8 +188,20 @@ class Stack:
                 out = bufs[flip] if cur.shape == bufs[flip].shape else torch.empty_like(cur)
                 if out.data_ptr() == cur.data_ptr():
                     out = torch.empty_like(cur)
+                if self.recompute:
+                    # saves made while a backward scope is open are kept on the device (Sec. 3.2)
+                    sb.ssdt_scope_begin(ctx, i, sb.BWD)
+                    ins = []
+                    for name in ("x", "enc"):
+                        ent = l.saved.e[sb.SV_NAMES.index(name)]
+                        ins.append(sb.ssdt_get(ctx, ent.tid, self.stream) if ent.tid else (ent.ptr or 0))
+                    y2, l.saved = sb.ssdt_layer_fwd(ctx, l.desc, l.wstruct, i, ins[0], ins[1], kvp, self.ws_ptr,
+                                                    self.ws_bytes, self.stream)
+                    sb.ssdt_arena_free(ctx, y2, self.stream)
                 sb.ssdt_layer_bwd(ctx, l.desc, l.wstruct, l.saved, kvp, cur.data_ptr(), out.data_ptr(), denc_ptr,
                                   l.gstruct, self.ws_ptr, self.ws_bytes, self.stream)
+                if self.recompute:
+                    sb.ssdt_scope_end(ctx, i, sb.BWD)
                 sb.ssdt_release(ctx, i, self.stream)
                 cur, flip = out, flip ^ 1
             return cur

@@ -132,6 +132,38 @@ def test_spill_file_tier_is_transparent(tmp_path):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_layerwise_recomputation_is_transparent_and_saves_memory(dtype):
+    """Recompute arm (Sec. 4.3): only layer inputs survive the forward pass (and are offloaded like any other
+    tensor); each layer is re-run inside its backward scope.  Same kernels on the same inputs, so outputs and
+    gradients equal the keep-everything run bit for bit, with a far lower activation peak."""
+    mk = lambda: [runner.Layer("gpt_preln", dtype, B=2, S=128, H=128, A=2, F=256, act="gelu", norm="layernorm",
+                               mask="causal", has_bias=True, eps=1e-5) for _ in range(4)]
+    cases = [hp.make_layer_case(l, 300 + i, bias_std=0.05) for i, l in enumerate(mk())]
+    x = runner.to_device(cases[0]["x"], dtype, DEV)
+    dy = runner.to_device(cases[0]["dy"], dtype, DEV)
+    per = runner.saved_bytes_per_layer(mk()[0])
+    res = {}
+    for name in ("keep", "recompute"):
+        ls = mk()
+        st = build(ls, cases, 8 * per, 5 * per, keep_last=1, min_offload_elems=0,
+                   budget_bytes=0 if name == "keep" else -1)
+        st.recompute = name == "recompute"
+        res[name] = run_gpu(st, ls, x, dy)
+        st.close()
+    assert torch.equal(res["keep"][0], res["recompute"][0]) and torch.equal(res["keep"][1], res["recompute"][1])
+    for ga, gb in zip(res["keep"][3], res["recompute"][3]):
+        for k in ga:
+            assert torch.equal(ga[k], gb[k]), k
+    fwd, fin = res["recompute"][4], res["recompute"][6]
+    xbytes = x.numel() * x.element_size()
+    assert (fwd["save_calls"], fwd["unique"], fwd["offloaded"], fwd["kept"]) == (4, 4, 3, 1)
+    assert fwd["bytes_offloaded"] == 3 * xbytes
+    assert (fin["save_calls"], fin["unique"], fin["dedup_hits"]) == (4 + 4 * 16, 4 * 13, 4 * 4)
+    assert fin["offloaded"] == 3 and fin["kept"] + fin["bypass_small"] == 1 + 4 * 12   # recomputed tensors stay put
+    assert fin["arena_peak_in_use"] < 0.5 * res["keep"][6]["arena_peak_in_use"]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_t5_encoder_decoder_stack(dtype):
     B, S, Se, H, A, F = 2, 128, 256, 128, 2, 256
     def mk():

@@ -160,3 +160,31 @@ def test_table3_sanity_ratio():
         run_layers(reg, [tr] * L)
         ratio = reg.c.bytes_offloaded / (cse["offloaded_GB"] * 1e9)
         assert 1.0 <= ratio <= 2.0, (H, ratio)
+
+
+def test_saves_during_backward_are_kept_hand_worked():
+    """Layerwise recomputation (Sec. 3.2, second condition of the keep test; Sec. 4.3): forward registers only
+    each layer's input; the recomputed activations registered inside backward never go to the pool."""
+    reg = ro.RegistryOracle(num_layers=2, min_offload_elems=0, budget_bytes=None, keep_last=0, pool_bytes=1 << 20)
+    for l in range(2):                                   # forward: one 1000-byte input per layer
+        reg.scope_begin(l)
+        assert reg.save(("x", l), 1000, 500) == l + 1
+        reg.scope_end(l)
+    assert (reg.c.offloaded, reg.c.bytes_offloaded, reg.c.kept) == (2, 2000, 0)
+    assert [r.pool_offset for r in reg.records] == [0, 4096]
+    reg.backward_begin()                                 # backward of layer 1: recompute, then backward
+    reg.scope_begin(1)
+    assert reg.save(("x", 1), 1000, 500) == 2            # the input again: the same record
+    assert reg.save(("h", 1), 3000, 1500) == 3           # recomputed activation: new stamp, kept
+    assert reg.save(("h", 1), 3000, 750) == 3
+    reg.scope_end(1)
+    reg.backward_end()
+    c = reg.c
+    assert (c.save_calls, c.unique, c.dedup_hits, c.offloaded, c.kept, c.bytes_kept, c.bytes_offloaded) == \
+           (5, 3, 2, 2, 1, 3000, 2000)
+    h = reg.records[2]
+    assert (h.cls, h.layer, h.pack_offset, h.pool_offset, h.scopes) == (ro.KEPT, 1, -1, -1, [1])
+    assert c.pool_bytes_used == 8192                     # the pool layout of the forward pass is untouched
+    # outside backward the same save is offloaded again
+    reg.scope_begin(1)
+    assert reg.save(("g", 1), 100, 50) == 4 and reg.records[3].cls == ro.OFFLOADED

@@ -52,7 +52,7 @@ def test_struct_layouts_match_the_header():
     assert ctypes.sizeof(sb.ssdt_config) == 64
     assert ctypes.sizeof(sb.ssdt_stats) == 22 * 8
     assert ctypes.sizeof(sb.ssdt_record) == 56
-    assert ctypes.sizeof(sb.ssdt_layer_desc) == 56
+    assert ctypes.sizeof(sb.ssdt_layer_desc) == 64
     assert ctypes.sizeof(sb.ssdt_layer_weights) == 20 * 8
     assert ctypes.sizeof(sb.ssdt_layer_saved) == 8 + 24 * sb.SV_COUNT
     assert sb.SV_COUNT == 24
@@ -399,4 +399,54 @@ def test_spill_write_failure_is_reported():
     with pytest.raises(sb.SsdtError) as e:
         sb.ssdt_prefetch(ctx, 1)
     assert e.value.status == sb.E_IO
+    sb.ssdt_ctx_destroy(ctx)
+
+
+def test_recompute_inside_backward_keeps_everything_and_matches_checker():
+    """Layerwise full recomputation through the registry: forward saves only each layer's input, the
+    layer's own saves repeat inside its backward scope and stay on the device (Sec. 3.2, Sec. 4.3)."""
+    B, S, H, A, F, e, L = 2, 16, 32, 4, 128, 2, 3
+    T = B * S
+    tr = ro.saved_trace("gpt_preln", "layernorm", "gelu", T, H, F, B, A, S, e)
+    ctx, ar = make(arena_bytes=4 << 20, pool_bytes=2 << 20, min_offload_elems=0, keep_last=1, budget_bytes=-1)
+    sb.ssdt_step_begin(ctx, L)
+    reg = ro.RegistryOracle(L, 0, None, 1, 2 << 20)
+    xs = {}
+    for l in range(L):                                    # forward: inputs only
+        xs[l] = sb.ssdt_arena_alloc(ctx, T * H * e)
+        sb.ssdt_scope_begin(ctx, l); reg.scope_begin(l)
+        assert sb.ssdt_save(ctx, xs[l], T * H * e, 0, [T * H], sb.BF16) == reg.save((l, "x"), T * H * e, T * H)
+        sb.ssdt_scope_end(ctx, l); reg.scope_end(l)
+        sb.ssdt_offload(ctx, l)
+        sb.ssdt_arena_free(ctx, xs[l])                    # the caller's reference; the record keeps its own
+    sb.ssdt_sync_io(ctx)
+    st = sb.ssdt_get_stats(ctx)
+    assert st["offloaded"] == L - 1 and st["kept"] == 1 and st["arena_in_use"] == T * H * e  # the kept last input
+    for l in range(L - 1, -1, -1):                        # backward: reload the input, recompute, release
+        sb.ssdt_prefetch(ctx, l)
+        sb.ssdt_scope_begin(ctx, l, sb.BWD); reg.backward_begin()
+        tid = [r for r in records(ctx) if r["layer"] == l][0]["tid"]
+        x = sb.ssdt_get(ctx, tid)
+        ptrs = {"x": x}
+        sb.ssdt_scope_begin(ctx, l); reg.scope_begin(l)
+        for name, storage, sbytes, numel in tr:
+            if storage not in ptrs:
+                ptrs[storage] = sb.ssdt_arena_alloc(ctx, sbytes)
+            dt = sb.F32 if storage.startswith(("mean", "rstd", "lse")) else sb.BF16
+            assert sb.ssdt_save(ctx, ptrs[storage], sbytes, 0, [numel], dt) == reg.save((l, storage), sbytes, numel)
+        sb.ssdt_scope_end(ctx, l); reg.scope_end(l)
+        for k, p in ptrs.items():
+            if k != "x":
+                sb.ssdt_arena_free(ctx, p)
+        sb.ssdt_scope_end(ctx, l, sb.BWD); reg.backward_end()
+        sb.ssdt_release(ctx, l)
+    compare_counts = sb.ssdt_get_stats(ctx)
+    for k, v in vars(reg.c).items():
+        assert compare_counts[k] == v, (k, compare_counts[k], v)
+    recs = records(ctx)
+    assert len(recs) == len(reg.records) == L * 13
+    assert [r["cls"] for r in recs[L:]] == [sb.CLS_KEPT if w.cls == ro.KEPT else sb.CLS_SMALL for w in reg.records[L:]]
+    assert all(w.cls != ro.OFFLOADED for w in reg.records[L:])
+    assert compare_counts["offloaded"] == L - 1 and compare_counts["loads"] == L - 1
+    assert compare_counts["arena_in_use"] == 0
     sb.ssdt_ctx_destroy(ctx)
