@@ -24,6 +24,26 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
+TRAFFIC_RECORD = os.path.join(ROOT, "profiles", "traffic_gemm_nt256_k__gpt_8192_b16.md")
+
+
+def recorded_traffic(kernel, workload, B):
+    """HBM bytes per launch of the dominant kernel from the committed counter summary; None when there is no
+    summary for this kernel / workload or when the kernel's source has changed since the counters were taken."""
+    import hashlib
+    import re
+    if kernel != "gemm_nt256_k" or workload != "gpt_8192" or B != 16 or not os.path.exists(TRAFFIC_RECORD):
+        return None
+    txt = open(TRAFFIC_RECORD).read()
+    m = {k: re.search(r"^%s:\s*(\S+)" % k, txt, re.M) for k in ("traffic_bytes_per_launch", "kernel_source_sha256")}
+    if not all(m.values()):
+        return None
+    src = os.path.join(ROOT, "paper_2408_10013_amd", "csrc", "kernels_mfma.hip")
+    if hashlib.sha256(open(src, "rb").read()).hexdigest() != m["kernel_source_sha256"].group(1):
+        return None
+    return float(m["traffic_bytes_per_launch"].group(1))
+
+
 MFMA_BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16
 HOST_LINK_PEAK_GBPS = 64.0          # PCIe 5.0 x16, per direction
 
@@ -53,7 +73,7 @@ def cpu_baseline(cfg, seconds_hint=20.0):
     from oracle import layer_oracle as lo
     from paper_2408_10013_amd import synth
     arch = cfg["stack"][0][0]
-    B, S = 1, 128
+    B, S = 1, 1024   # about 10-20 s of host work at the headline widths
     d = lo.LayerDesc(arch=arch, B=B, S=S, H=cfg["H"], A=cfg["A"], F=cfg["F"], act=cfg["act"], norm=cfg["norm"],
                      mask="causal" if cfg["mask"] == "causal" else "none", has_bias=cfg["has_bias"], eps=cfg["eps"])
     shapes = lo.weight_shapes(d)
@@ -99,6 +119,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sweep", default="", help="comma-separated micro-batch sizes: one off/budget measurement per size "
                                                 "(throughput and activation memory vs micro-batch), printed as one JSON line")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="run one 1 GiB device-to-device copy and exit: the kernel of known size that calibrates the "
+                         "HBM byte counters of a profiler run")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (one process, one MI355X, no collectives); "
@@ -114,6 +137,14 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     dev = torch.device("cuda:0")
+    if args.copy_probe:
+        a = torch.zeros(1 << 28, dtype=torch.float32, device=dev)
+        b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe_bytes_read": a.numel() * 4, "copy_probe_bytes_written": a.numel() * 4}))
+        return
     cfg = synth.CONFIGS[args.workload]
     dtype = cfg["dtype"]
     tdt = torch.float32 if dtype == "f32" else torch.bfloat16
@@ -253,7 +284,8 @@ def main():
         if dom:
             ach = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
             roof = {"kernel": dom["name"], "bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS,
-                    "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                    "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
+                    "traffic": recorded_traffic(dom["name"], args.workload, B) if L == len(cfg["stack"]) else None,
                     "launches": dom["launches"], "avg_launch_ms": dom["ms"] / dom["launches"]}
     cpu = None if args.no_cpu_baseline else cpu_baseline(cfg)
     out = {
