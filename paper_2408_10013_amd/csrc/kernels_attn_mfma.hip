@@ -170,13 +170,13 @@ __global__ __launch_bounds__(256, 2) void fa_fwd_k(FaP p) {
       }
     mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
     const float mnew = fmaxf(m, mloc), msafe = (mnew == -INFINITY) ? 0.f : mnew;
-    const float corr = exp2f(m - msafe);
+    const float corr = __builtin_amdgcn_exp2f(m - msafe);
     float lsum = 0.f;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        float e = exp2f(sacc[kb][r] - msafe);
+        float e = __builtin_amdgcn_exp2f(sacc[kb][r] - msafe);
         sacc[kb][r] = e;
         lsum += e;
       }
@@ -250,10 +250,16 @@ hipError_t attn_fwd_mfma_bf16(const Attn &a, hipStream_t s) {
 // ------------------------------------------------------------------------------------------
 // backward, key side: one workgroup = 128 keys of one (sequence, head), each wavefront 32 keys;
 // loops over 64-query tiles of Q and dO.  dK[j] = scale sum_i dS_ij q_i, dV[j] = sum_i P_ij dO_i.
+// Two wavefronts per SIMD matter more here than anything else (one wavefront alone cannot hide its
+// LDS and MFMA latencies: measured 229 vs 290 TFLOP/s), so with head size 128, where the two
+// 32 x 128 accumulators already take 128 registers, the kernel runs lean: the block's V rows stay in
+// LDS instead of registers and the next Q / dO tile is not prefetched into registers.
 // ------------------------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(256, (D == 128 ? 1 : 2)) void fa_bwd_dkv_k(FaP p) {
+__global__ __launch_bounds__(256, 2) void fa_bwd_dkv_k(FaP p) {
   constexpr int BQ = 64, LQ = D + 8, KS = D / 16, DB = D / 32;
+  constexpr bool LEAN = D > 64;
+  __shared__ __attribute__((aligned(16))) uint16_t sV[LEAN ? 128 * LQ : 8];
   __shared__ __attribute__((aligned(16))) uint16_t sQ[BQ * LQ];
   __shared__ __attribute__((aligned(16))) uint16_t sdO[BQ * LQ];
   __shared__ __attribute__((aligned(16))) float sLse[BQ], sDelta[BQ];
@@ -263,12 +269,14 @@ __global__ __launch_bounds__(256, (D == 128 ? 1 : 2)) void fa_bwd_dkv_k(FaP p) {
   int limit = p.Sk;
   if (p.mask == SSDT_MASK_KEYPAD) limit = min(limit, max(0, p.kv_len[b]));
   const uint16_t *kp = p.k + (long)(b * p.Sk + kj) * p.ldk + h * D, *vp = p.v + (long)(b * p.Sk + kj) * p.ldv + h * D;
-  bf16x8_t kf[KS], vf[KS];
+  bf16x8_t kf[KS], vf[LEAN ? 1 : KS];
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) {
     kf[ks] = *(const bf16x8_t *)(kp + ks * 16 + half * 8);
-    vf[ks] = *(const bf16x8_t *)(vp + ks * 16 + half * 8);
+    if (!LEAN) vf[ks] = *(const bf16x8_t *)(vp + ks * 16 + half * 8);
   }
+  if (LEAN) load_tile<D, 128, LQ>(p.v + (long)(b * p.Sk + blockIdx.x * 128) * p.ldv + h * D, p.ldv, 128, sV, tid);
+  const uint16_t *vrow = sV + (w * 32 + li) * LQ + half * 8;  // this lane's V row (lean variant)
   f32x16_t dkacc[DB], dvacc[DB];
 #pragma unroll
   for (int d = 0; d < DB; ++d)
@@ -284,7 +292,7 @@ __global__ __launch_bounds__(256, (D == 128 ? 1 : 2)) void fa_bwd_dkv_k(FaP p) {
   const int tstart = block_live ? t0 : nt;
   uint4 rq[BQ * (D / 8) / 256], rdo[BQ * (D / 8) / 256];
   float rstat = 0.f;
-  if (tstart < nt) {
+  if (!LEAN && tstart < nt) {
     tile_gload<D, BQ>(qg + (long)tstart * BQ * p.ldq, p.ldq, BQ, tid, rq);
     tile_gload<D, BQ>(dog + (long)tstart * BQ * p.lddo, p.lddo, BQ, tid, rdo);
     if (tid < BQ) rstat = lse_g[tstart * BQ + tid];
@@ -293,12 +301,19 @@ __global__ __launch_bounds__(256, (D == 128 ? 1 : 2)) void fa_bwd_dkv_k(FaP p) {
   for (int t = tstart; t < nt; ++t) {
     const int i0 = t * BQ;
     __syncthreads();
-    tile_sstore<D, BQ, LQ>(sQ, tid, rq);
-    tile_sstore<D, BQ, LQ>(sdO, tid, rdo);
-    if (tid < BQ) sLse[tid] = rstat;
-    else if (tid < 2 * BQ) sDelta[tid - BQ] = rstat;
+    if (LEAN) {
+      load_tile<D, BQ, LQ>(qg + (long)i0 * p.ldq, p.ldq, BQ, sQ, tid);
+      load_tile<D, BQ, LQ>(dog + (long)i0 * p.lddo, p.lddo, BQ, sdO, tid);
+      if (tid < BQ) sLse[tid] = lse_g[i0 + tid];
+      else if (tid < 2 * BQ) sDelta[tid - BQ] = delta_g[i0 + tid - BQ];
+    } else {
+      tile_sstore<D, BQ, LQ>(sQ, tid, rq);
+      tile_sstore<D, BQ, LQ>(sdO, tid, rdo);
+      if (tid < BQ) sLse[tid] = rstat;
+      else if (tid < 2 * BQ) sDelta[tid - BQ] = rstat;
+    }
     __syncthreads();
-    if (t + 1 < nt) {
+    if (!LEAN && t + 1 < nt) {
       tile_gload<D, BQ>(qg + (long)(i0 + BQ) * p.ldq, p.ldq, BQ, tid, rq);
       tile_gload<D, BQ>(dog + (long)(i0 + BQ) * p.lddo, p.lddo, BQ, tid, rdo);
       if (tid < BQ) rstat = lse_g[i0 + BQ + tid];
@@ -306,7 +321,7 @@ __global__ __launch_bounds__(256, (D == 128 ? 1 : 2)) void fa_bwd_dkv_k(FaP p) {
     }
     if (p.mask == SSDT_MASK_CAUSAL && i0 + BQ - 1 < k0) continue;  // every query of the tile precedes this wavefront's keys
     const bool need_mask = (p.mask == SSDT_MASK_CAUSAL && i0 < k0 + 31) || (k0 + 32 > limit);
-#pragma unroll
+#pragma unroll(LEAN ? 1 : 2)
     for (int qb = 0; qb < 2; ++qb) {
       f32x16_t sacc, dpacc;
 #pragma unroll
@@ -315,9 +330,11 @@ __global__ __launch_bounds__(256, (D == 128 ? 1 : 2)) void fa_bwd_dkv_k(FaP p) {
       for (int ks = 0; ks < KS; ++ks) {
         bf16x8_t qa = *(const bf16x8_t *)(sQ + (qb * 32 + li) * LQ + ks * 16 + half * 8);
         bf16x8_t da = *(const bf16x8_t *)(sdO + (qb * 32 + li) * LQ + ks * 16 + half * 8);
+        const bf16x8_t vv = LEAN ? *(const bf16x8_t *)(vrow + ks * 16) : vf[ks];
         sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kf[ks], sacc, 0, 0, 0);
-        dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(da, vf[ks], dpacc, 0, 0, 0);
+        dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(da, vv, dpacc, 0, 0, 0);
       }
+      if (LEAN) __builtin_amdgcn_sched_barrier(0);  // keeps the fragment reads of the next phase from being hoisted
       // this lane: key kj, queries i0 + qb*32 + g*8 + half*4 + 0..3
       float pv[16], dsv[16];
 #pragma unroll
@@ -328,7 +345,7 @@ __global__ __launch_bounds__(256, (D == 128 ? 1 : 2)) void fa_bwd_dkv_k(FaP p) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int r = g * 4 + e;
-          float pe = exp2f(sacc[r] * sc - lv[e] * kLog2e);
+          float pe = __builtin_amdgcn_exp2f(sacc[r] * sc - lv[e] * kLog2e);
           bool dead = lv[e] == -INFINITY;
           if (need_mask) dead = dead || kj >= limit || (p.mask == SSDT_MASK_CAUSAL && kj > i0 + qo + e);
           pe = dead ? 0.f : pe;
@@ -346,6 +363,7 @@ __global__ __launch_bounds__(256, (D == 128 ? 1 : 2)) void fa_bwd_dkv_k(FaP p) {
           dvacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dot, pf, dvacc[d], 0, 0, 0);
           bf16x8_t qt = frag_tr(sQ, LQ, klo, klo + 8, d * 32, lane);
           dkacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qt, dsf, dkacc[d], 0, 0, 0);
+          if (LEAN && (d & 1)) __builtin_amdgcn_sched_barrier(0);
         }
       }
     }
@@ -432,7 +450,7 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dq_k(FaP p) {
       float dsv[16];
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        float pe = exp2f(sacc[r] * sc - lse2);
+        float pe = __builtin_amdgcn_exp2f(sacc[r] * sc - lse2);
         bool dead = row_dead;
         if (need_mask) {
           const int key = j0 + kb * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
