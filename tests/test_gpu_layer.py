@@ -169,6 +169,29 @@ def test_layer_variants_small(name, dtype):
         assert torch.equal(on["d_enc"], off["d_enc"])
 
 
+@pytest.mark.parametrize("name", ["bert_keypad", "bert_mfma"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_sequence_without_any_admissible_key(name, dtype):
+    """Degenerate case of the key-padding mask: one sequence of valid length 0.  Every one of its query rows has
+    no key to attend to: probabilities and attention output are exactly 0 there, lse is -inf, and no gradient
+    flows through its attention (the convention written in the checker's header); the other sequences are
+    unaffected.  Covers both attention paths (generic and matrix-core)."""
+    v = dict(VARIANTS[name])
+    l = runner.Layer(dtype=dtype, **v)
+    case = hp.make_layer_case(l, 3000 + len(name), bias_std=0.05, kv_len_range=(1, v["S"]))
+    case["kv_len"] = case["kv_len"].copy()
+    case["kv_len"][1] = 0
+    for k in case["w"]:
+        if k.startswith("w_"):
+            case["w"][k] = synth.bf16_round(case["w"][k] * 4) if dtype == "bf16" else case["w"][k] * 4
+    on = run_single_layer(l, case, offload=True)
+    check_against_oracle(l, case, on, hp.TOL[dtype])
+    S, H = v["S"], v["H"]
+    lse = on["saved"]["lse"]
+    assert np.all(np.isneginf(lse[1])) and np.all(np.isfinite(lse[0])) and np.all(np.isfinite(lse[2]))
+    assert not np.any(on["saved"]["o"][S:2 * S])          # exact zeros
+
+
 @pytest.mark.parametrize("name", list(VARIANTS))
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_backward_from_checker_saved(name, dtype):

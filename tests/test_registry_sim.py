@@ -450,3 +450,25 @@ def test_recompute_inside_backward_keeps_everything_and_matches_checker():
     assert compare_counts["offloaded"] == L - 1 and compare_counts["loads"] == L - 1
     assert compare_counts["arena_in_use"] == 0
     sb.ssdt_ctx_destroy(ctx)
+
+
+def test_layer_descriptors_are_validated_without_a_gpu():
+    """ssdt_layer_workspace checks a descriptor with the same rules as the layer entry points."""
+    good = dict(arch="gpt_preln", dtype="bf16", B=2, S=128, H=256, A=4, F=1024)
+    f, b = sb.ssdt_layer_workspace(sb.make_desc(**good))
+    assert f > 0 and b >= f                      # transposed-operand scratch; backward needs the gradient temporaries too
+    for bad in (dict(B=0), dict(S=0), dict(H=0), dict(A=0), dict(F=0), dict(A=3), dict(B=-1), dict(eps=0.0)):
+        with pytest.raises(sb.SsdtError) as e:
+            sb.ssdt_layer_workspace(sb.make_desc(**{**good, **bad}))
+        assert e.value.status == sb.E_INVAL, bad
+    d = sb.make_desc(**good)
+    d.arch = 17
+    with pytest.raises(sb.SsdtError) as e:
+        sb.ssdt_layer_workspace(d)
+    assert e.value.status == sb.E_INVAL
+    with pytest.raises(sb.SsdtError) as e:       # a decoder layer needs the encoder length
+        sb.ssdt_layer_workspace(sb.make_desc(**{**good, "arch": "t5_dec", "S_kv": 0}))
+    assert e.value.status == sb.E_INVAL
+    with pytest.raises(sb.SsdtError) as e:       # more tokens than the kernels index
+        sb.ssdt_layer_workspace(sb.make_desc(**{**good, "B": 1 << 20, "S": 1 << 12}))
+    assert e.value.status == sb.E_UNSUPPORTED
