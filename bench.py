@@ -285,7 +285,7 @@ def main():
             ach = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
             roof = {"kernel": dom["name"], "bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS,
                     "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
-                    "traffic": recorded_traffic(dom["name"], args.workload, B) if L == len(cfg["stack"]) else None,
+                    "traffic": recorded_traffic(dom["name"], args.workload, B),
                     "launches": dom["launches"], "avg_launch_ms": dom["ms"] / dom["launches"]}
     cpu = None if args.no_cpu_baseline else cpu_baseline(cfg)
     out = {
