@@ -160,13 +160,10 @@ __device__ __forceinline__ void epilogue_staged(const NtP &p, const f32x16_t (&a
 }
 
 // ------------------------------------------------------------------------------------------
-// 256x256 tile, 8 wavefronts (each 128x64), 64-wide K steps, direct global-to-LDS loads.
-// The LDS holds five 32 KiB half-stages (all A rows or all Bt rows of one K step) used in rotation:
-// step k reads halves (2k) % 5 and (2k+1) % 5, step k+1's are loading or loaded next to them, and
-// the fifth half takes the A rows of step k+2 without waiting for anybody to finish reading, so half
-// of every stage's loads get a whole extra step to land.
+// 256x256 tile, 8 wavefronts, two 64-wide LDS stages of direct global-to-LDS loads
 // ------------------------------------------------------------------------------------------
 constexpr int kBM2 = 256, kBN2 = 256, kBK2 = 64;
+constexpr int kStage2 = (kBM2 + kBN2) * kBK2;  // elements per stage: A rows then Bt rows, 128 bytes each
 
 __device__ __forceinline__ bf16x8_t as_bf(v4i_t v) {
   union { v4i_t a; bf16x8_t b; } u;
@@ -182,23 +179,17 @@ __device__ __forceinline__ bf16x8_t as_bf(v4i_t v) {
   }
 #define SSDT_WAIT6(N, A0, A1, A2, A3, B0, B1)                                                             \
   asm volatile("s_waitcnt lgkmcnt(" #N ")" : "+v"(A0), "+v"(A1), "+v"(A2), "+v"(A3), "+v"(B0), "+v"(B1))
-// the eight MFMAs of a sub-step in two halves (A fragments 0, 1 / 2, 3), so that a load can go out in between
-#define SSDT_MFMA4A(A0, A1, B0, B1)                                                                       \
+#define SSDT_MFMA8(A0, A1, A2, A3, B0, B1)                                                                \
   {                                                                                                       \
     acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(B0), as_bf(A0), acc[0][0], 0, 0, 0);        \
     acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(B1), as_bf(A0), acc[0][1], 0, 0, 0);        \
     acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(B0), as_bf(A1), acc[1][0], 0, 0, 0);        \
     acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(B1), as_bf(A1), acc[1][1], 0, 0, 0);        \
-  }
-#define SSDT_MFMA4B(A2, A3, B0, B1)                                                                       \
-  {                                                                                                       \
     acc[2][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(B0), as_bf(A2), acc[2][0], 0, 0, 0);        \
     acc[2][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(B1), as_bf(A2), acc[2][1], 0, 0, 0);        \
     acc[3][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(B0), as_bf(A3), acc[3][0], 0, 0, 0);        \
     acc[3][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(B1), as_bf(A3), acc[3][1], 0, 0, 0);        \
   }
-
-constexpr int kHalf = kBM2 * kBK2;  // elements per half-stage (kBM2 == kBN2)
 
 template <int EPI>
 __global__ __launch_bounds__(512) void gemm_nt256_k(NtP p) {
@@ -207,14 +198,24 @@ __global__ __launch_bounds__(512) void gemm_nt256_k(NtP p) {
   int tile_m, tile_n;
   tile_of(p, blockIdx.x, &tile_m, &tile_n);
   const int m0 = tile_m * kBM2, n0 = tile_n * kBN2;
+
+  // loader: thread t fills LDS positions j*512 + t (16-byte units), j = 0..3, of A and of Bt:
+  // row j*64 + t/8, slot t%8, which holds global chunk (t%8) ^ ((row >> 1) & 7) of that row;
+  // 8 consecutive lanes fetch one whole 128-byte line
   const int lrow = tid >> 3, lchunk = (tid & 7) ^ ((lrow >> 1) & 7);
   const uint16_t *ga = p.A + (long)(m0 + lrow) * p.lda + lchunk * 8;
   const uint16_t *gb = p.Bt + (long)(n0 + lrow) * p.ldb + lchunk * 8;
   const long a64 = 64 * p.lda, b64 = 64 * p.ldb;
-  uint16_t *s_wave = smem + wave * 64 * 8;
-// load j (64-row slice) of the A / Bt half of step kt into half-stage hb
-#define SSDT_LD_A(kt, hb, j) __builtin_amdgcn_global_load_lds(ga + (j) * a64 + (long)(kt) * kBK2, (lds_void_t *)(s_wave + (hb) * kHalf + (j) * 64 * kBK2), 16, 0, 0)
-#define SSDT_LD_B(kt, hb, j) __builtin_amdgcn_global_load_lds(gb + (j) * b64 + (long)(kt) * kBK2, (lds_void_t *)(s_wave + (hb) * kHalf + (j) * 64 * kBK2), 16, 0, 0)
+  uint16_t *s_wave = smem + wave * 64 * 8;  // a wavefront's 64 positions are contiguous: 1 KiB per load
+// two of the eight loads of a stage: the 64-row slices j of A and of Bt
+#define SSDT_ISSUE2(kt, j)                                                                                \
+  {                                                                                                       \
+    uint16_t *sb_ = s_wave + ((kt) & 1) * kStage2 + (j) * 64 * kBK2;                                      \
+    const long ko_ = (long)(kt) * kBK2;                                                                   \
+    __builtin_amdgcn_global_load_lds(ga + (j) * a64 + ko_, (lds_void_t *)(sb_), 16, 0, 0);                \
+    __builtin_amdgcn_global_load_lds(gb + (j) * b64 + ko_, (lds_void_t *)(sb_ + kBM2 * kBK2), 16, 0, 0);  \
+  }
+#define SSDT_ISSUE(kt) { SSDT_ISSUE2(kt, 0); SSDT_ISSUE2(kt, 1); SSDT_ISSUE2(kt, 2); SSDT_ISSUE2(kt, 3); }
 
   f32x16_t acc[4][2];
 #pragma unroll
@@ -225,96 +226,65 @@ __global__ __launch_bounds__(512) void gemm_nt256_k(NtP p) {
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   const int nk = p.K / kBK2;
-  // prologue: stage 0 into halves 0 and 1, the A rows of stage 1 into half 2
-  SSDT_LD_A(0, 0, 0); SSDT_LD_A(0, 0, 1); SSDT_LD_A(0, 0, 2); SSDT_LD_A(0, 0, 3);
-  SSDT_LD_B(0, 1, 0); SSDT_LD_B(0, 1, 1); SSDT_LD_B(0, 1, 2); SSDT_LD_B(0, 1, 3);
-  if (nk > 1) { SSDT_LD_A(1, 2, 0); SSDT_LD_A(1, 2, 1); SSDT_LD_A(1, 2, 2); SSDT_LD_A(1, 2, 3); }
+  SSDT_ISSUE(0);
 
   const int li = lane & 31, half = lane >> 5;
   const unsigned sw = (li >> 1) & 7;
   const unsigned lds0 = (unsigned)(uintptr_t)smem;
-  const unsigned arow = lds0 + (wm * 128 + li) * 128, brow = lds0 + (wn * 64 + li) * 128;
+  // LDS byte addresses (stage 0) of this lane's first A / Bt fragment rows for the four sub-steps
+  const unsigned arow = lds0 + (wm * 128 + li) * 128, brow = lds0 + (kBM2 + wn * 64 + li) * 128;
   const unsigned oa0 = arow + ((0 + half) ^ sw) * 16, oa1 = arow + ((2 + half) ^ sw) * 16;
   const unsigned oa2 = arow + ((4 + half) ^ sw) * 16, oa3 = arow + ((6 + half) ^ sw) * 16;
   const unsigned ob0 = brow + ((0 + half) ^ sw) * 16, ob1 = brow + ((2 + half) ^ sw) * 16;
   const unsigned ob2 = brow + ((4 + half) ^ sw) * 16, ob3 = brow + ((6 + half) ^ sw) * 16;
   v4i_t pa0, pa1, pa2, pa3, pb0, pb1, qa0, qa1, qa2, qa3, qb0, qb1;
 
-  if (nk > 1) __builtin_amdgcn_s_waitcnt(0xF74);  // vmcnt(4): all but the four youngest loads (A of stage 1)
-  else __builtin_amdgcn_s_waitcnt(0xF70);
+  // Software pipeline over the 64-wide stages.  A stage's four 16-wide sub-steps alternate between the
+  // register sets P and Q.  The wait for the next stage (its loads have landed, everyone is done reading
+  // the current one) sits BEFORE the last sub-step's MFMAs, once this wavefront holds all operands of the
+  // current stage: the first fragments of the next stage are then read under those MFMAs instead of under
+  // an idle matrix pipe.  The loads of the stage after next go out in small groups (1, 2, 1 pairs) at the
+  // barrier and in the first two sub-steps: a burst of all eight holds back the MFMAs queued behind it,
+  // a later issue leaves them too little time before the wait.
+  __builtin_amdgcn_s_waitcnt(0xF70);
   __builtin_amdgcn_s_barrier();
-  // Software pipeline.  A step's four 16-wide sub-steps alternate between the register sets P and Q, read two
-  // sub-steps ahead.  The hand-over to the next step (its loads have landed for everyone, everyone is done
-  // reading the current one) sits BEFORE the last sub-step's MFMAs, once this wavefront holds all operands of the
-  // current step, so the first fragments of the next step are read under those MFMAs.  The eight loads a
-  // wavefront issues per step go out one at a time, each followed by four MFMAs, in the order Bt 0 1 | 2 3 (step
-  // kt+1, the first two right after the hand-over) and A 0 1 | 2 3 (step kt+2, into the spare half): bursts of
-  // loads hold back the MFMAs queued behind them and were measured 5-10 % slower.  Loads return in order, so at
-  // the hand-over "all but the four youngest" (the A loads of step kt+2) is exactly "step kt+1 has landed".
-  // hA: half holding the A rows of the current step; its Bt rows are in hA+1, the next step's in hA+2 and hA+3,
-  // the spare is hA+4 (all mod 5).
-  int hA = 0;
-  if (nk > 1) { SSDT_LD_B(1, 3, 0); SSDT_LD_B(1, 3, 1); }
-  SSDT_READ6(pa0, pa1, pa2, pa3, pb0, pb1, oa0, ob0 + kHalf * 2);
+  if (nk > 1) SSDT_ISSUE2(1, 0);
+  SSDT_READ6(pa0, pa1, pa2, pa3, pb0, pb1, oa0, ob0);
   for (int kt = 0; kt < nk; ++kt) {
-    const int hB = hA + 1 >= 5 ? hA - 4 : hA + 1, hA1 = hA + 2 >= 5 ? hA - 3 : hA + 2, hB1 = hA + 3 >= 5 ? hA - 2 : hA + 3,
-              hS = hA + 4 >= 5 ? hA - 1 : hA + 4;
-    const unsigned sa = hA * (kHalf * 2), sbb = hB * (kHalf * 2);
+    const unsigned so = (kt & 1) * kStage2 * 2, so1 = ((kt + 1) & 1) * kStage2 * 2;
     const bool more = kt + 1 < nk, more2 = kt + 2 < nk;
-    // sub-step 0
-    SSDT_READ6(qa0, qa1, qa2, qa3, qb0, qb1, oa1 + sa, ob1 + sbb);
+    SSDT_READ6(qa0, qa1, qa2, qa3, qb0, qb1, oa1 + so, ob1 + so);
     SSDT_WAIT6(6, pa0, pa1, pa2, pa3, pb0, pb1);
-    if (more) SSDT_LD_B(kt + 1, hB1, 2);
+    if (more) { SSDT_ISSUE2(kt + 1, 1); SSDT_ISSUE2(kt + 1, 2); }
     __builtin_amdgcn_sched_barrier(0);
-    SSDT_MFMA4A(pa0, pa1, pb0, pb1);
+    SSDT_MFMA8(pa0, pa1, pa2, pa3, pb0, pb1);
     __builtin_amdgcn_sched_barrier(0);
-    if (more) SSDT_LD_B(kt + 1, hB1, 3);
-    __builtin_amdgcn_sched_barrier(0);
-    SSDT_MFMA4B(pa2, pa3, pb0, pb1);
-    __builtin_amdgcn_sched_barrier(0);
-    // sub-step 1
-    SSDT_READ6(pa0, pa1, pa2, pa3, pb0, pb1, oa2 + sa, ob2 + sbb);
+    SSDT_READ6(pa0, pa1, pa2, pa3, pb0, pb1, oa2 + so, ob2 + so);
     SSDT_WAIT6(6, qa0, qa1, qa2, qa3, qb0, qb1);
-    if (more2) SSDT_LD_A(kt + 2, hS, 0);
+    if (more) SSDT_ISSUE2(kt + 1, 3);
     __builtin_amdgcn_sched_barrier(0);
-    SSDT_MFMA4A(qa0, qa1, qb0, qb1);
+    SSDT_MFMA8(qa0, qa1, qa2, qa3, qb0, qb1);
     __builtin_amdgcn_sched_barrier(0);
-    if (more2) SSDT_LD_A(kt + 2, hS, 1);
-    __builtin_amdgcn_sched_barrier(0);
-    SSDT_MFMA4B(qa2, qa3, qb0, qb1);
-    __builtin_amdgcn_sched_barrier(0);
-    // sub-step 2
-    SSDT_READ6(qa0, qa1, qa2, qa3, qb0, qb1, oa3 + sa, ob3 + sbb);
+    SSDT_READ6(qa0, qa1, qa2, qa3, qb0, qb1, oa3 + so, ob3 + so);
     SSDT_WAIT6(6, pa0, pa1, pa2, pa3, pb0, pb1);
-    if (more2) SSDT_LD_A(kt + 2, hS, 2);
     __builtin_amdgcn_sched_barrier(0);
-    SSDT_MFMA4A(pa0, pa1, pb0, pb1);
+    SSDT_MFMA8(pa0, pa1, pa2, pa3, pb0, pb1);
     __builtin_amdgcn_sched_barrier(0);
-    if (more2) SSDT_LD_A(kt + 2, hS, 3);
-    __builtin_amdgcn_sched_barrier(0);
-    SSDT_MFMA4B(pa2, pa3, pb0, pb1);
-    __builtin_amdgcn_sched_barrier(0);
-    // sub-step 3, with the hand-over in front of its MFMAs
-    SSDT_WAIT6(0, qa0, qa1, qa2, qa3, qb0, qb1);  // this wavefront holds everything it needs of step kt
+    SSDT_WAIT6(0, qa0, qa1, qa2, qa3, qb0, qb1);  // this wavefront now holds everything it needs of stage kt
     if (more) {
-      if (more2) __builtin_amdgcn_s_waitcnt(0xF74);  // vmcnt(4)
-      else __builtin_amdgcn_s_waitcnt(0xF70);        // vmcnt(0): no loads of a step kt+2 are in flight
-      __builtin_amdgcn_s_barrier();                  // step kt+1 is in the LDS for everyone; half hA is free
-      if (more2) SSDT_LD_B(kt + 2, hA, 0);
-      SSDT_READ6(pa0, pa1, pa2, pa3, pb0, pb1, oa0 + hA1 * (kHalf * 2), ob0 + hB1 * (kHalf * 2));
+      __builtin_amdgcn_s_waitcnt(0xF70);  // vmcnt(0): its part of stage kt+1 has landed
+      __builtin_amdgcn_s_barrier();       // so has everyone's; and everyone is done reading stage kt
+      if (more2) SSDT_ISSUE2(kt + 2, 0);
+      SSDT_READ6(pa0, pa1, pa2, pa3, pb0, pb1, oa0 + so1, ob0 + so1);
     }
     __builtin_amdgcn_sched_barrier(0);
-    SSDT_MFMA4A(qa0, qa1, qb0, qb1);
+    SSDT_MFMA8(qa0, qa1, qa2, qa3, qb0, qb1);
     __builtin_amdgcn_sched_barrier(0);
-    if (more2) SSDT_LD_B(kt + 2, hA, 1);
-    __builtin_amdgcn_sched_barrier(0);
-    SSDT_MFMA4B(qa2, qa3, qb0, qb1);
-    __builtin_amdgcn_sched_barrier(0);
-    hA = hA1;
   }
-#undef SSDT_LD_A
-#undef SSDT_LD_B
-  __builtin_amdgcn_s_barrier();
+#undef SSDT_ISSUE2
+#undef SSDT_ISSUE
+  // epilogue through LDS (free now), two 64-row halves of the wavefront's 128x64 tile
+  __builtin_amdgcn_s_barrier();  // every wavefront has finished reading the last stage
   float *stg = (float *)smem + wave * (64 * kEpiLd);
   epilogue_staged<EPI>(p, acc[0], acc[1], stg, m0 + wm * 128, n0 + wn * 64, lane);
   epilogue_staged<EPI>(p, acc[2], acc[3], stg, m0 + wm * 128 + 64, n0 + wn * 64, lane);
@@ -402,8 +372,7 @@ __global__ __launch_bounds__(256) void gemm_nt128_k(NtP p) {
 
 template <int EPI>
 static hipError_t launch256(const NtP &p, hipStream_t s) {
-  constexpr size_t stages = (size_t)5 * kHalf * 2, stage_out = (size_t)8 * 64 * kEpiLd * 4;  // 160 KiB of half-stages; epilogue staging reuses it
-  constexpr size_t smem = stage_out > stages ? stage_out : stages;
+  constexpr size_t smem = (size_t)8 * 64 * kEpiLd * 4 > (size_t)2 * kStage2 * 2 ? (size_t)8 * 64 * kEpiLd * 4 : (size_t)2 * kStage2 * 2;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void *)gemm_nt256_k<EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
