@@ -117,6 +117,8 @@ typedef struct ssdt_record {
   int64_t pack_offset;    /* offset in its layer's pack, -1 unless OFFLOADED class */
   int64_t pool_offset;    /* offset in the host pool (= offset in the spill file) */
   void *device_ptr;       /* current device address or NULL */
+  int32_t micro_batch;    /* micro-batch that was current at its first save */
+  int32_t reserved;
 } ssdt_record;
 
 const char *ssdt_last_error(const ssdt_ctx *ctx); /* HOST string owned by the context; "" if none */
@@ -136,6 +138,15 @@ ssdt_status ssdt_ctx_destroy(ssdt_ctx *ctx);
  * refers to them).  Clears the step's records and counters; E_STATE if records of the previous step
  * have not been released. */
 ssdt_status ssdt_step_begin(ssdt_ctx *ctx, int32_t num_layers);
+/* Switches to the records of micro-batch `mb` (Sec. 3.1: individual records are kept for each micro-batch and
+ * the cache switches to the one of the new micro-batch when the scheduler changes micro-batch).  Every scope id
+ * passed afterwards (scope_begin/end, offload, prefetch, release, the layer entry points) refers to that
+ * micro-batch, so the records of several micro-batches can be alive between their forward and their backward.
+ * `keep_last` >= 0 overrides ssdt_config.keep_last for this micro-batch (the paper keeps the last module only
+ * where its backward follows its forward immediately); < 0 keeps the configured value.  ssdt_step_begin
+ * selects micro-batch 0 and forgets the overrides.  E_STATE while a scope is open or before ssdt_step_begin;
+ * E_INVAL for mb outside [0, 2^20). Scope ids must be below 2^20. */
+ssdt_status ssdt_micro_batch(ssdt_ctx *ctx, int32_t mb, int32_t keep_last);
 /* Changes the per-step offload amount (same meaning as ssdt_config.budget_bytes). */
 ssdt_status ssdt_set_budget(ssdt_ctx *ctx, int64_t budget_bytes);
 

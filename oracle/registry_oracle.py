@@ -23,6 +23,13 @@ Rules, in the order the pack hook applies them to one save call:
      checkpointed module recomputing its activations: second condition of the pack
      hook's keep test, Sec. 3.2); otherwise it is OFFLOADED and `offloaded_so_far += bytes`
 
+Micro-batches (Sec. 3.1: individual records are kept for each micro-batch and the cache switches
+records when the micro-batch changes): `micro_batch(mb)` makes every later scope id refer to that
+micro-batch, so the same layer ids can be open for several micro-batches at once; the keep-last
+rule can be overridden per micro-batch (the paper keeps the last module only where its backward
+follows its forward immediately); stamps, the offload amount and the pool cursor run across
+micro-batches.
+
 Host-pool layout: the OFFLOADED storages of one layer (the scope at the bottom of the
 scope stack) form a pack, in first-save order, each starting at the next multiple of
 256 bytes; a pack's size is rounded up to 4096 bytes; packs follow each other in the
@@ -52,6 +59,7 @@ class Record:
     pack_offset: int = -1      # offset inside the layer's pack (OFFLOADED only)
     pool_offset: int = -1      # offset inside the host pool   (OFFLOADED only)
     scopes: List[int] = field(default_factory=list)
+    micro_batch: int = 0
 
 
 @dataclass
@@ -88,12 +96,21 @@ class RegistryOracle:
         self.pack_base: Dict[int, int] = {}       # layer -> pool offset of its pack
         self.pool_cursor = 0
         self.in_backward = 0                      # depth of open backward scopes
+        self.cur_mb = 0
+        self.mb_keep_last: Dict[int, int] = {}
 
     # -- events ------------------------------------------------------------------------
     def register_weight(self, storage) -> None:
         self.weights.add(storage)
 
+    def micro_batch(self, mb: int, keep_last: Optional[int] = None) -> None:
+        assert not self.stack and self.in_backward == 0
+        self.cur_mb = mb
+        if keep_last is not None:
+            self.mb_keep_last[mb] = keep_last
+
     def scope_begin(self, scope: int) -> None:
+        scope = (self.cur_mb, scope)
         if not self.stack and scope not in self.pack_base:
             # a new layer: its pack starts where the previous layer's (rounded) pack ended
             self.pool_cursor = _up(self.pool_cursor, ALIGN_PACK)
@@ -109,6 +126,7 @@ class RegistryOracle:
         self.in_backward -= 1
 
     def scope_end(self, scope: int) -> None:
+        scope = (self.cur_mb, scope)
         assert self.stack and self.stack[-1] == scope
         self.stack.pop()
         if not self.stack:
@@ -125,10 +143,12 @@ class RegistryOracle:
         rec = self.by_storage.get(storage)
         if rec is not None:
             c.dedup_hits += 1
-            if scope not in rec.scopes:
-                rec.scopes.append(scope)
+            assert rec.micro_batch == scope[0], "a storage is saved from one micro-batch only"
+            if scope[1] not in rec.scopes:
+                rec.scopes.append(scope[1])
             return 0 if rec.cls == SMALL else rec.stamp
-        rec = Record(stamp=self.next_stamp, cls=KEPT, layer=layer, bytes=storage_bytes, scopes=[scope])
+        rec = Record(stamp=self.next_stamp, cls=KEPT, layer=layer[1], micro_batch=layer[0], bytes=storage_bytes,
+                     scopes=[scope[1]])
         self.next_stamp += 1
         self.by_storage[storage] = rec
         self.records.append(rec)
@@ -138,7 +158,7 @@ class RegistryOracle:
             c.bypass_small += 1
             c.bytes_small += storage_bytes
             return 0
-        in_last = layer >= self.num_layers - self.keep_last
+        in_last = layer[1] >= self.num_layers - self.mb_keep_last.get(layer[0], self.keep_last)
         over = self.budget is not None and c.bytes_offloaded + storage_bytes > self.budget
         off = _up(self.pack_cursor[layer], ALIGN_TENSOR)
         nomem = (self.pool_bytes is not None and
@@ -161,14 +181,15 @@ class RegistryOracle:
         """Stamps of a layer's OFFLOADED records in the order they are loaded: the reverse
         of the order they were saved in, because backward consumes them last-in-first-out
         (Sec. 3.1 step 5; Sec. 3.3.2)."""
-        return [r.stamp for r in reversed(self.records) if r.layer == layer and r.cls == OFFLOADED]
+        return [r.stamp for r in reversed(self.records)
+                if r.layer == layer and r.micro_batch == self.cur_mb and r.cls == OFFLOADED]
 
     def release(self, scope: int) -> List[int]:
         """Backward of `scope` finished: drop it from every scope list; returns the stamps
         whose list became empty (their memory is freed) -- Sec. 3.2, backward hook pair."""
         freed = []
         for r in self.records:
-            if scope in r.scopes:
+            if r.micro_batch == self.cur_mb and scope in r.scopes:
                 r.scopes.remove(scope)
                 if not r.scopes:
                     freed.append(r.stamp)

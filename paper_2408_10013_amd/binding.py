@@ -61,7 +61,8 @@ class ssdt_stats(C.Structure):
 class ssdt_record(C.Structure):
     _fields_ = [("tid", C.c_uint64), ("layer", C.c_int32), ("cls", C.c_int32), ("state", C.c_int32),
                 ("n_scopes", C.c_int32), ("bytes", C.c_uint64), ("pack_offset", C.c_int64),
-                ("pool_offset", C.c_int64), ("device_ptr", C.c_void_p)]
+                ("pool_offset", C.c_int64), ("device_ptr", C.c_void_p), ("micro_batch", C.c_int32),
+                ("reserved", C.c_int32)]
 
 
 class ssdt_plan_in(C.Structure):
@@ -106,6 +107,7 @@ _PROTOS = {
     "ssdt_ctx_create": (C.c_int32, [C.POINTER(ssdt_config), C.POINTER(C.c_void_p)]),
     "ssdt_ctx_destroy": (C.c_int32, [C.c_void_p]),
     "ssdt_step_begin": (C.c_int32, [C.c_void_p, C.c_int32]),
+    "ssdt_micro_batch": (C.c_int32, [C.c_void_p, C.c_int32, C.c_int32]),
     "ssdt_set_budget": (C.c_int32, [C.c_void_p, C.c_int64]),
     "ssdt_arena_alloc": (C.c_int32, [C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(C.c_void_p)]),
     "ssdt_arena_free": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_void_p]),
@@ -186,6 +188,10 @@ def ssdt_ctx_destroy(ctx):
 
 def ssdt_step_begin(ctx, num_layers):
     _check(ctx, lib().ssdt_step_begin(ctx, num_layers), "ssdt_step_begin")
+
+
+def ssdt_micro_batch(ctx, mb, keep_last=-1):
+    _check(ctx, lib().ssdt_micro_batch(ctx, mb, keep_last), "ssdt_micro_batch")
 
 
 def ssdt_set_budget(ctx, budget_bytes):

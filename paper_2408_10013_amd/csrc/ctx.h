@@ -66,7 +66,8 @@ struct Block {
 
 struct Rec {
   ssdt_tid tid = 0;
-  int32_t layer = 0, cls = 0, state = 0;
+  int64_t layer = 0;          // owning layer, as a key: (micro-batch << 20) | layer index
+  int32_t cls = 0, state = 0;
   uint64_t bytes = 0;
   int64_t pack_offset = -1, pool_offset = -1;
   void *dev = nullptr;
@@ -78,7 +79,7 @@ struct Rec {
   bool load_waited = false;
   bool spill_deferred = false; // spill mode: dropped from the device before its copy out was seen finished
   bool read_pending = false;  // spill mode: the file read of this record has been requested, its copy not yet issued
-  std::vector<int32_t> scopes;
+  std::vector<int64_t> scopes;  // scope keys: (micro-batch << 20) | scope
   Ev *store_ev = nullptr, *load_ev = nullptr;
 };
 
@@ -123,13 +124,21 @@ struct Ctx {
   // registry
   int32_t num_layers = 0;
   std::vector<std::pair<const char *, size_t>> weights;
-  std::vector<int32_t> stack;
-  std::vector<int32_t> bwd_open;
+  std::vector<int64_t> stack;     // open forward scopes (keys)
+  std::vector<int64_t> bwd_open;  // open backward scopes (keys)
+  // Records are kept per micro-batch (Sec. 3.1): every scope id the caller passes is combined with the current
+  // micro-batch into a key, so that several micro-batches can be between their forward and their backward.
+  int32_t cur_mb = 0;
+  std::map<int32_t, int32_t> mb_keep_last;  // per-micro-batch override of cfg.keep_last
+  static constexpr int kScopeBits = 20;
+  int64_t key(int32_t scope) const { return ((int64_t)cur_mb << kScopeBits) | (int64_t)scope; }
+  static int32_t scope_of(int64_t k) { return (int32_t)(k & ((1 << kScopeBits) - 1)); }
+  static int32_t mb_of(int64_t k) { return (int32_t)(k >> kScopeBits); }
   uint64_t next_stamp = 1;
   std::vector<Rec> recs;
   std::unordered_map<const void *, size_t> by_storage;
   std::unordered_map<ssdt_tid, size_t> by_tid;
-  std::map<int32_t, size_t> pack_base, pack_cursor;
+  std::map<int64_t, size_t> pack_base, pack_cursor;  // by layer key
   size_t pool_cursor = 0;
   std::deque<size_t> storing;  // record indices with a store in flight, oldest first
   ssdt_stats st{};
@@ -160,6 +169,7 @@ struct Ctx {
   ssdt_status get(ssdt_tid tid, ssdt_stream consumer, void **out);
   ssdt_status release(int32_t scope, ssdt_stream s);
   ssdt_status step_begin(int32_t n);
+  ssdt_status micro_batch(int32_t mb, int32_t keep_last);
   void timed_wait(ssdt_stream s, Ev *e, int kind);
   ssdt_status spill_open(const char *path);
   void spill_close();

@@ -392,6 +392,8 @@ ssdt_status Ctx::step_begin(int32_t n) {
   pack_cursor.clear();
   storing.clear();
   bwd_open.clear();
+  cur_mb = 0;
+  mb_keep_last.clear();
   pool_cursor = 0;
   num_layers = n;
   ssdt_stats z{};
@@ -403,8 +405,18 @@ ssdt_status Ctx::step_begin(int32_t n) {
   return SSDT_OK;
 }
 
-ssdt_status Ctx::scope_begin(int32_t scope, int32_t phase) {
-  if (scope < 0) return fail(SSDT_E_INVAL, "scope_begin: negative scope");
+ssdt_status Ctx::micro_batch(int32_t mb, int32_t keep_last) {
+  if (mb < 0 || mb >= (1 << 20)) return fail(SSDT_E_INVAL, "micro_batch: id out of range");
+  if (!stack.empty() || !bwd_open.empty()) return fail(SSDT_E_STATE, "micro_batch: a scope is still open");
+  if (num_layers <= 0) return fail(SSDT_E_STATE, "micro_batch: no step in progress (call ssdt_step_begin)");
+  cur_mb = mb;
+  if (keep_last >= 0) mb_keep_last[mb] = keep_last;
+  return SSDT_OK;
+}
+
+ssdt_status Ctx::scope_begin(int32_t scope_id, int32_t phase) {
+  if (scope_id < 0 || scope_id >= (1 << kScopeBits)) return fail(SSDT_E_INVAL, "scope_begin: scope id out of range");
+  const int64_t scope = key(scope_id);
   if (phase == SSDT_FWD) {
     if (num_layers <= 0) return fail(SSDT_E_STATE, "scope_begin: no step in progress (call ssdt_step_begin)");
     if (stack.empty() && !pack_base.count(scope)) {
@@ -422,17 +434,18 @@ ssdt_status Ctx::scope_begin(int32_t scope, int32_t phase) {
   return fail(SSDT_E_INVAL, "scope_begin: unknown phase %d", phase);
 }
 
-ssdt_status Ctx::scope_end(int32_t scope, int32_t phase) {
+ssdt_status Ctx::scope_end(int32_t scope_id, int32_t phase) {
+  const int64_t scope = key(scope_id);
   if (phase == SSDT_FWD) {
     if (stack.empty() || stack.back() != scope)
-      return fail(SSDT_E_STATE, "scope_end: scope %d is not on top of the forward scope stack", scope);
+      return fail(SSDT_E_STATE, "scope_end: scope %d is not on top of the forward scope stack", scope_id);
     stack.pop_back();
     if (stack.empty()) pool_cursor = up(pack_base[scope] + pack_cursor[scope], kAlignPack);
     return SSDT_OK;
   }
   if (phase == SSDT_BWD) {
     if (bwd_open.empty() || bwd_open.back() != scope)
-      return fail(SSDT_E_STATE, "scope_end: backward scope %d is not open", scope);
+      return fail(SSDT_E_STATE, "scope_end: backward scope %d is not open", scope_id);
     bwd_open.pop_back();
     return SSDT_OK;
   }
@@ -463,7 +476,7 @@ ssdt_status Ctx::save(const void *base, size_t sbytes, size_t view_off, const in
     *out = 0;
     return SSDT_OK;
   }
-  int32_t scope = stack.back(), layer = stack.front();
+  const int64_t scope = stack.back(), layer = stack.front();
   auto hit = by_storage.find(base);
   if (hit != by_storage.end()) {  // a view of a storage already stamped (Sec. 3.3.1)
     Rec &r = recs[hit->second];
@@ -491,7 +504,8 @@ ssdt_status Ctx::save(const void *base, size_t sbytes, size_t view_off, const in
     st.bytes_small += sbytes;
     *out = 0;
   } else {
-    bool in_last = layer >= num_layers - cfg.keep_last;
+    auto kl = mb_keep_last.find(mb_of(layer));
+    bool in_last = scope_of(layer) >= num_layers - (kl != mb_keep_last.end() ? kl->second : cfg.keep_last);
     bool over = cfg.budget_bytes >= 0 && st.bytes_offloaded + sbytes > (uint64_t)cfg.budget_bytes;
     size_t off = up(pack_cursor[layer], kAlignTensor);
     bool nomem = up(pack_base[layer] + off + sbytes, kAlignPack) > cfg.pool_bytes;
@@ -517,7 +531,8 @@ ssdt_status Ctx::save(const void *base, size_t sbytes, size_t view_off, const in
   return SSDT_OK;
 }
 
-ssdt_status Ctx::offload(int32_t scope, ssdt_stream producer) {
+ssdt_status Ctx::offload(int32_t scope_id, ssdt_stream producer) {
+  const int64_t scope = key(scope_id);
   poll();
   if (ssdt_status e = spill_status("offload")) return e;
   Ev *after = nullptr;
@@ -539,7 +554,8 @@ ssdt_status Ctx::offload(int32_t scope, ssdt_stream producer) {
   return SSDT_OK;
 }
 
-ssdt_status Ctx::prefetch(int32_t scope) {
+ssdt_status Ctx::prefetch(int32_t scope_id) {
+  const int64_t scope = key(scope_id);
   poll();
   if (ssdt_status e = spill_status("prefetch")) return e;
   std::vector<size_t> todo;
@@ -617,7 +633,8 @@ ssdt_status Ctx::get(ssdt_tid tid, ssdt_stream consumer, void **out) {
   return SSDT_OK;
 }
 
-ssdt_status Ctx::release(int32_t scope, ssdt_stream s) {
+ssdt_status Ctx::release(int32_t scope_id, ssdt_stream s) {
+  const int64_t scope = key(scope_id);
   poll();
   Ev *ev = nullptr;
   for (auto &r : recs) {
@@ -706,6 +723,8 @@ ssdt_status ssdt_ctx_destroy(ssdt_ctx *ctx) {
 
 ssdt_status ssdt_step_begin(ssdt_ctx *c, int32_t n) { return c ? c->step_begin(n) : SSDT_E_INVAL; }
 
+ssdt_status ssdt_micro_batch(ssdt_ctx *c, int32_t mb, int32_t keep_last) { return c ? c->micro_batch(mb, keep_last) : SSDT_E_INVAL; }
+
 ssdt_status ssdt_set_budget(ssdt_ctx *c, int64_t b) {
   if (!c) return SSDT_E_INVAL;
   c->cfg.budget_bytes = b;
@@ -788,7 +807,9 @@ ssdt_status ssdt_get_record(const ssdt_ctx *c, uint32_t i, ssdt_record *out) {
   if (i >= c->recs.size()) return SSDT_E_NOTFOUND;
   const Rec &r = c->recs[i];
   out->tid = r.tid;
-  out->layer = r.layer;
+  out->layer = Ctx::scope_of(r.layer);
+  out->micro_batch = Ctx::mb_of(r.layer);
+  out->reserved = 0;
   out->cls = r.cls;
   out->state = r.state;
   out->n_scopes = (int32_t)r.scopes.size();

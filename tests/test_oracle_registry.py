@@ -188,3 +188,32 @@ def test_saves_during_backward_are_kept_hand_worked():
     # outside backward the same save is offloaded again
     reg.scope_begin(1)
     assert reg.save(("g", 1), 100, 50) == 4 and reg.records[3].cls == ro.OFFLOADED
+
+
+def test_two_micro_batches_in_flight_hand_worked():
+    """Individual records per micro-batch (Sec. 3.1): forward of micro-batch 0, forward of micro-batch 1, then the
+    backwards in reverse.  Same layer ids, separate records; stamps, the offload amount and the pool run across both;
+    the last layer is kept only for the micro-batch whose backward follows at once."""
+    reg = ro.RegistryOracle(num_layers=2, min_offload_elems=0, budget_bytes=2500, keep_last=1, pool_bytes=1 << 20)
+    reg.micro_batch(0, keep_last=0)               # its backward is far away: nothing kept for being last
+    for l in range(2):
+        reg.scope_begin(l)
+        assert reg.save(("a", 0, l), 1000, 500) == l + 1
+        reg.scope_end(l)
+    reg.micro_batch(1)                            # default keep_last = 1
+    for l in range(2):
+        reg.scope_begin(l)
+        assert reg.save(("a", 1, l), 1000, 500) == l + 3
+        reg.scope_end(l)
+    rec = reg.records
+    assert [(r.micro_batch, r.layer, r.cls) for r in rec] == \
+        [(0, 0, ro.OFFLOADED), (0, 1, ro.OFFLOADED), (1, 0, ro.KEPT), (1, 1, ro.KEPT)]
+    # micro-batch 1, layer 0: 2000 + 1000 > 2500 -> over the amount; layer 1: last layer of its micro-batch
+    assert [r.pool_offset for r in rec] == [0, 4096, -1, -1]
+    assert reg.c.pool_bytes_used == 8192 and reg.c.bytes_offloaded == 2000 and reg.c.bytes_kept == 2000
+    # releases address the current micro-batch only
+    assert reg.release(1) == [4] and reg.release(0) == [3]
+    reg.micro_batch(0)
+    assert reg.prefetch_order(1) == [2] and reg.prefetch_order(0) == [1]
+    assert reg.release(1) == [2] and reg.release(0) == [1]
+    assert all(not r.scopes for r in rec)

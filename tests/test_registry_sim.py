@@ -51,7 +51,7 @@ def test_library_exports_every_declared_symbol():
 def test_struct_layouts_match_the_header():
     assert ctypes.sizeof(sb.ssdt_config) == 64
     assert ctypes.sizeof(sb.ssdt_stats) == 22 * 8
-    assert ctypes.sizeof(sb.ssdt_record) == 56
+    assert ctypes.sizeof(sb.ssdt_record) == 64
     assert ctypes.sizeof(sb.ssdt_layer_desc) == 64
     assert ctypes.sizeof(sb.ssdt_layer_weights) == 20 * 8
     assert ctypes.sizeof(sb.ssdt_layer_saved) == 8 + 24 * sb.SV_COUNT
@@ -472,3 +472,59 @@ def test_layer_descriptors_are_validated_without_a_gpu():
     with pytest.raises(sb.SsdtError) as e:       # more tokens than the kernels index
         sb.ssdt_layer_workspace(sb.make_desc(**{**good, "B": 1 << 20, "S": 1 << 12}))
     assert e.value.status == sb.E_UNSUPPORTED
+
+
+def test_records_per_micro_batch_match_checker():
+    """Two micro-batches between forward and backward at the same time (Sec. 3.1): forward 0, forward 1, backward
+    1, backward 0, with the layer traces of a GPT layer; bookkeeping against the checker, and the data of each
+    micro-batch comes back to its own records."""
+    B, S, H, A, F, e, L = 2, 16, 32, 4, 128, 2, 2
+    T = B * S
+    tr = ro.saved_trace("gpt_preln", "layernorm", "gelu", T, H, F, B, A, S, e)
+    ctx, ar = make(arena_bytes=4 << 20, pool_bytes=2 << 20, min_offload_elems=0, keep_last=1, budget_bytes=-1)
+    sb.ssdt_step_begin(ctx, L)
+    reg = ro.RegistryOracle(L, 0, None, 1, 2 << 20)
+    tids = {}
+    for mb, kl in ((0, 0), (1, -1)):
+        sb.ssdt_micro_batch(ctx, mb, kl); reg.micro_batch(mb, None if kl < 0 else kl)
+        for l in range(L):
+            sb.ssdt_scope_begin(ctx, l); reg.scope_begin(l)
+            ptrs = {}
+            for name, storage, sbytes, numel in tr:
+                if storage not in ptrs:
+                    ptrs[storage] = sb.ssdt_arena_alloc(ctx, sbytes)
+                    ar.view(ptrs[storage], sbytes)[:] = (17 * mb + 5 * l + len(ptrs)) & 0xFF
+                dt = sb.F32 if storage.startswith(("mean", "rstd", "lse")) else sb.BF16
+                got = sb.ssdt_save(ctx, ptrs[storage], sbytes, 0, [numel], dt)
+                assert got == reg.save((mb, l, storage), sbytes, numel)
+                tids[(mb, l, storage)] = (got, sbytes, (17 * mb + 5 * l + list(ptrs).index(storage) + 1) & 0xFF)
+            sb.ssdt_scope_end(ctx, l); reg.scope_end(l)
+            sb.ssdt_offload(ctx, l)
+            for p in ptrs.values():
+                sb.ssdt_arena_free(ctx, p)
+    compare(ctx, reg)
+    recs = records(ctx)
+    assert [r["micro_batch"] for r in recs] == [0] * 26 + [1] * 26
+    assert sum(1 for r in recs if r["cls"] == sb.CLS_KEPT) == 13         # only the last layer of micro-batch 1
+    sb.ssdt_sync_io(ctx)
+    for mb in (1, 0):
+        sb.ssdt_micro_batch(ctx, mb)
+        for l in (1, 0):
+            sb.ssdt_prefetch(ctx, l)
+            for (m2, l2, storage), (tid, sbytes, fill) in tids.items():
+                if (m2, l2) == (mb, l):
+                    p = sb.ssdt_get(ctx, tid)
+                    assert bytes(ar.view(p, sbytes)) == bytes([fill]) * sbytes, (mb, l, storage)
+            sb.ssdt_release(ctx, l)
+    st = sb.ssdt_get_stats(ctx)
+    assert st["arena_in_use"] == 0 and st["released"] == 52 and st["loads"] == 39
+    with pytest.raises(sb.SsdtError) as e:
+        sb.ssdt_micro_batch(ctx, -1)
+    assert e.value.status == sb.E_INVAL
+    sb.ssdt_scope_begin(ctx, 0)
+    with pytest.raises(sb.SsdtError) as e:
+        sb.ssdt_micro_batch(ctx, 1)
+    assert e.value.status == sb.E_STATE
+    sb.ssdt_scope_end(ctx, 0)
+    sb.ssdt_step_begin(ctx, L)
+    sb.ssdt_ctx_destroy(ctx)
