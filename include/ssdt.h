@@ -289,7 +289,10 @@ typedef struct ssdt_layer_desc {
                                   backward and frees every intermediate; the caller recomputes the layer
                                   inside its backward scope before ssdt_layer_bwd (layerwise full
                                   recomputation, the comparison arm of Sec. 4.3) */
-  int32_t reserved;
+  int32_t accumulate;          /* nonzero: ssdt_layer_bwd adds the weight, bias and norm-parameter gradients to what
+                                  `grads` holds instead of overwriting it (gradient accumulation over the
+                                  micro-batches of a step, Sec. 1); the sum is rounded to the tensors' type once
+                                  per call */
 } ssdt_layer_desc;
 
 /* DEVICE pointers, element type = desc.dtype.  Matrices are row-major [in, out] (y = x W + b);
@@ -354,6 +357,12 @@ ssdt_status ssdt_layer_bwd(ssdt_ctx *ctx, const ssdt_layer_desc *desc, const ssd
                            const ssdt_layer_saved *saved, const int32_t *kv_len, const void *dy, void *dx,
                            void *d_enc_out, const ssdt_layer_weights *grads, void *ws, size_t ws_bytes,
                            ssdt_stream stream);
+
+/* Plain SGD step on one parameter tensor: w <- w - lr * g elementwise, computed in fp32 and stored in `dtype`
+ * (Sec. 4.1: the evaluation uses SGD so that the optimizer adds no state).  `w`, `g`: DEVICE, `numel` elements of
+ * `dtype` (SSDT_F32 / SSDT_BF16), caller-owned; enqueued on `stream`.  E_INVAL for null pointers or an unknown
+ * dtype, E_UNSUPPORTED on the simulated backend. */
+ssdt_status ssdt_sgd_update(ssdt_ctx *ctx, void *w, const void *g, size_t numel, int32_t dtype, float lr, ssdt_stream stream);
 
 #ifdef __cplusplus
 }

@@ -84,7 +84,7 @@ class ssdt_kernel_time(C.Structure):
 class ssdt_layer_desc(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("arch", "dtype", "act", "norm", "mask", "has_bias", "B", "S", "S_kv", "H",
                                          "A", "F")] + [("eps", C.c_float), ("softmax_scale", C.c_float),
-                                                        ("checkpoint", C.c_int32), ("reserved", C.c_int32)]
+                                                        ("checkpoint", C.c_int32), ("accumulate", C.c_int32)]
 
 
 class ssdt_layer_weights(C.Structure):
@@ -130,6 +130,7 @@ _PROTOS = {
     "ssdt_spill_stats": (C.c_int32, [C.c_void_p, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)]),
     "ssdt_profile": (C.c_int32, [C.c_void_p, C.c_int32]),
     "ssdt_profile_read": (C.c_int32, [C.c_void_p, C.POINTER(ssdt_kernel_time), C.c_uint32, C.POINTER(C.c_uint32)]),
+    "ssdt_sgd_update": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_int32, C.c_float, C.c_void_p]),
     "ssdt_layer_workspace": (C.c_int32, [C.POINTER(ssdt_layer_desc), C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]),
     "ssdt_layer_fwd": (C.c_int32, [C.c_void_p, C.POINTER(ssdt_layer_desc), C.POINTER(ssdt_layer_weights), C.c_int32,
                                    C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_void_p),
@@ -312,9 +313,9 @@ def ssdt_profile_read(ctx) -> list:
 
 
 def make_desc(arch="gpt_preln", dtype="f32", act="gelu", norm="layernorm", mask="causal", has_bias=True, B=1, S=1,
-              S_kv=0, H=1, A=1, F=1, eps=1e-5, softmax_scale=0.0, checkpoint=False) -> ssdt_layer_desc:
+              S_kv=0, H=1, A=1, F=1, eps=1e-5, softmax_scale=0.0, checkpoint=False, accumulate=False) -> ssdt_layer_desc:
     return ssdt_layer_desc(ARCH[arch], DTYPE[dtype], ACT[act], NORM[norm], MASK[mask], int(bool(has_bias)), B, S, S_kv,
-                           H, A, F, eps, softmax_scale, int(bool(checkpoint)), 0)
+                           H, A, F, eps, softmax_scale, int(bool(checkpoint)), int(bool(accumulate)))
 
 
 def make_weights(ptrs: dict) -> ssdt_layer_weights:
@@ -322,6 +323,10 @@ def make_weights(ptrs: dict) -> ssdt_layer_weights:
     for n in WEIGHT_NAMES:
         setattr(w, n, ptrs.get(n) or None)
     return w
+
+
+def ssdt_sgd_update(ctx, w, g, numel, dtype, lr, stream=0):
+    _check(ctx, lib().ssdt_sgd_update(ctx, w, g, numel, dtype, lr, stream or None), "ssdt_sgd_update")
 
 
 def ssdt_layer_workspace(desc: ssdt_layer_desc):

@@ -57,9 +57,12 @@ hipError_t norm_fwd(const void *x, const void *gamma, const void *beta, void *y,
 // through `partial` (fp32, colreduce_partial_floats(rows, H) elements).
 hipError_t norm_bwd(const void *dy, const void *x, const float *mean, const float *rstd, const void *gamma,
                     const void *resid, void *dx, void *dgamma, void *dbeta, float *partial, int rows, int H, int kind,
-                    int dtype, hipStream_t s);
+                    int dtype, bool accumulate, hipStream_t s);
 // out[n] = sum_m a[m, n]  (bias gradients), same two-stage scheme
-hipError_t colsum(const void *a, long lda, void *out, float *partial, int rows, int cols, int dtype, hipStream_t s);
+hipError_t colsum(const void *a, long lda, void *out, float *partial, int rows, int cols, int dtype, bool accumulate,
+                  hipStream_t s);
+// w <- w - lr * g, elementwise in fp32, stored in the tensors' type
+hipError_t sgd_update(void *w, const void *g, size_t n, float lr, int dtype, hipStream_t s);
 size_t colreduce_partial_floats(int rows, int cols);
 
 struct Attn {

@@ -253,21 +253,22 @@ __global__ __launch_bounds__(256) void colreduce1_k(const T *a, long lda, const 
 }
 
 template <typename T>
-__global__ void colreduce2_k(const float *partial, int chunks, int cols, T *out_b, T *out_g) {
+__global__ void colreduce2_k(const float *partial, int chunks, int cols, T *out_b, T *out_g, int accumulate) {
   int c = blockIdx.x * blockDim.x + threadIdx.x;
   if (c >= cols) return;
   float b = 0.f, g = 0.f;
   for (int k = 0; k < chunks; ++k) b += partial[(size_t)k * cols + c];
-  if (out_b) st(out_b + c, b);
+  if (out_b) st(out_b + c, accumulate ? ld(out_b + c) + b : b);
   if (out_g) {
     for (int k = 0; k < chunks; ++k) g += partial[(size_t)(chunks + k) * cols + c];
-    st(out_g + c, g);
+    st(out_g + c, accumulate ? ld(out_g + c) + g : g);
   }
 }
 
 template <typename T>
 static hipError_t colreduce(const T *a, long lda, const T *x, const float *mean, const float *rstd, int kind,
-                            T *out_g, T *out_b, float *partial, int rows, int cols, bool norm, hipStream_t s) {
+                            T *out_g, T *out_b, float *partial, int rows, int cols, bool norm, bool accumulate,
+                            hipStream_t s) {
   int chunks = colreduce_chunks(rows);
   int rpc = (rows + chunks - 1) / chunks;
   dim3 grid((cols + 127) / 128, chunks);
@@ -279,14 +280,15 @@ static hipError_t colreduce(const T *a, long lda, const T *x, const float *mean,
     else hipLaunchKernelGGL((colreduce1_k<T, false>), grid, dim3(256), 0, s, a, lda, x, mean, rstd, kind, partial, rows, cols, rpc);
   }
   SSDT_LAUNCH_CHECK();
-  hipLaunchKernelGGL(colreduce2_k<T>, dim3((cols + 255) / 256), dim3(256), 0, s, (const float *)partial, chunks, cols, out_b, out_g);
+  hipLaunchKernelGGL(colreduce2_k<T>, dim3((cols + 255) / 256), dim3(256), 0, s, (const float *)partial, chunks, cols, out_b, out_g,
+                     accumulate ? 1 : 0);
   SSDT_LAUNCH_CHECK();
   return hipSuccess;
 }
 
 hipError_t norm_bwd(const void *dy, const void *x, const float *mean, const float *rstd, const void *gamma,
                     const void *resid, void *dx, void *dgamma, void *dbeta, float *partial, int rows, int H, int kind,
-                    int dtype, hipStream_t s) {
+                    int dtype, bool accumulate, hipStream_t s) {
   dim3 grid((rows + 3) / 4);
   hipError_t ev = dtype == SSDT_BF16 ? norm_bwd_dx_vec(dy, x, mean, rstd, gamma, resid, dx, rows, H, kind, s) : hipErrorNotSupported;
   if (ev != hipErrorNotSupported && ev != hipSuccess) return ev;
@@ -302,17 +304,18 @@ hipError_t norm_bwd(const void *dy, const void *x, const float *mean, const floa
   SSDT_LAUNCH_CHECK();
   if (dtype == SSDT_F32)
     return colreduce<float>((const float *)dy, H, (const float *)x, mean, rstd, kind, (float *)dgamma, (float *)dbeta,
-                            partial, rows, H, true, s);
+                            partial, rows, H, true, accumulate, s);
   return colreduce<bf16>((const bf16 *)dy, H, (const bf16 *)x, mean, rstd, kind, (bf16 *)dgamma, (bf16 *)dbeta, partial,
-                         rows, H, true, s);
+                         rows, H, true, accumulate, s);
 }
 
-hipError_t colsum(const void *a, long lda, void *out, float *partial, int rows, int cols, int dtype, hipStream_t s) {
+hipError_t colsum(const void *a, long lda, void *out, float *partial, int rows, int cols, int dtype, bool accumulate,
+                  hipStream_t s) {
   if (dtype == SSDT_F32)
     return colreduce<float>((const float *)a, lda, nullptr, nullptr, nullptr, 0, nullptr, (float *)out, partial, rows,
-                            cols, false, s);
+                            cols, false, accumulate, s);
   return colreduce<bf16>((const bf16 *)a, lda, nullptr, nullptr, nullptr, 0, nullptr, (bf16 *)out, partial, rows, cols,
-                         false, s);
+                         false, accumulate, s);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -626,6 +629,46 @@ hipError_t transpose(const void *in, long ldi, void *out, long ldo, int rows, in
     hipLaunchKernelGGL(transpose_k<uint32_t>, grid, dim3(256), 0, s, (const uint32_t *)in, ldi, (uint32_t *)out, ldo, rows, cols);
   else
     hipLaunchKernelGGL(transpose_k<uint16_t>, grid, dim3(256), 0, s, (const uint16_t *)in, ldi, (uint16_t *)out, ldo, rows, cols);
+  SSDT_LAUNCH_CHECK();
+  return hipSuccess;
+}
+
+template <typename T>
+__global__ void sgd_update_k(T *w, const T *g, size_t n, float lr) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) st(w + i, fmaf(-lr, ld(g + i), ld(w + i)));
+}
+// bf16, 16 bytes per access
+__global__ void sgd_update_bf16x8_k(uint4 *w, const uint4 *g, size_t n8, float lr) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n8; i += stride) {
+    uint4 a = w[i];
+    const uint4 b = g[i];
+    uint32_t *pa = (uint32_t *)&a;
+    const uint32_t *pb = (const uint32_t *)&b;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const float w0 = bf2f((uint16_t)(pa[t] & 0xffff)), w1 = bf2f((uint16_t)(pa[t] >> 16));
+      const float g0 = bf2f((uint16_t)(pb[t] & 0xffff)), g1 = bf2f((uint16_t)(pb[t] >> 16));
+      pa[t] = pack_bf2(fmaf(-lr, g0, w0), fmaf(-lr, g1, w1));
+    }
+    w[i] = a;
+  }
+}
+
+hipError_t sgd_update(void *w, const void *g, size_t n, float lr, int dtype, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  prof::Scope ps(prof::ADD, 0, 3.0 * n * (dtype == SSDT_F32 ? 4 : 2), s);
+  if (dtype == SSDT_BF16 && n % 8 == 0 && (((uintptr_t)w | (uintptr_t)g) & 15) == 0) {
+    size_t blocks = std::min<size_t>((n / 8 + 255) / 256, 16384);
+    hipLaunchKernelGGL(sgd_update_bf16x8_k, dim3((unsigned)blocks), dim3(256), 0, s, (uint4 *)w, (const uint4 *)g, n / 8, lr);
+  } else {
+    size_t blocks = std::min<size_t>((n + 255) / 256, 65536);
+    if (dtype == SSDT_F32) hipLaunchKernelGGL(sgd_update_k<float>, dim3((unsigned)blocks), dim3(256), 0, s, (float *)w, (const float *)g, n, lr);
+    else hipLaunchKernelGGL(sgd_update_k<bf16>, dim3((unsigned)blocks), dim3(256), 0, s, (bf16 *)w, (const bf16 *)g, n, lr);
+  }
   SSDT_LAUNCH_CHECK();
   return hipSuccess;
 }

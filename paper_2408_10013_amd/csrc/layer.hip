@@ -361,16 +361,19 @@ ssdt_status ssdt_layer_bwd(ssdt_ctx *ctx, const ssdt_layer_desc *desc, const ssd
     return k::gemm(g, st);
   };
   // gradients of y = in W + b given dY: dW = in^T dY, db = column sums of dY
+  // (with gradient accumulation the product is added to what dW holds: the residual epilogue reading dW itself)
+  const bool accum = desc->accumulate != 0;
   auto wgrad = [&](const void *in, int Kin, const void *dY, int Nout, int rows, void *dW, void *db) -> hipError_t {
-    hipError_t e1 = mm(Kin, Nout, rows, in, Kin, true, dY, Nout, false, dW, k::EPI_NONE, nullptr, nullptr);
+    hipError_t e1 = mm(Kin, Nout, rows, in, Kin, true, dY, Nout, false, dW, accum ? k::EPI_BIAS_RESID : k::EPI_NONE,
+                       accum ? dW : nullptr, nullptr);
     if (e1 != hipSuccess) return e1;
-    if (db) return k::colsum(dY, Nout, db, bf.partial, rows, Nout, dt, st);
+    if (db) return k::colsum(dY, Nout, db, bf.partial, rows, Nout, dt, accum, st);
     return hipSuccess;
   };
   auto nbwd = [&](const void *dout, const void *xin, const void *mean, const void *rstd, const void *gamma,
                   const void *resid, void *dxo, void *dgam, void *dbet) {
     return k::norm_bwd(dout, xin, (const float *)mean, (const float *)rstd, gamma, resid, dxo, dgam, D.ln ? dbet : nullptr,
-                       bf.partial, D.T, D.H, desc->norm, dt, st);
+                       bf.partial, D.T, D.H, desc->norm, dt, accum, st);
   };
   auto attn_b = [&](const void *q, long ldq, const void *kk, const void *v, long ldkv, int Sq, int Sk, int mask,
                     const void *o, const void *lse, const void *dO, void *dq, long lddq, void *dk, void *dv, long lddkv) {
@@ -467,6 +470,15 @@ ssdt_status ssdt_layer_bwd(ssdt_ctx *ctx, const ssdt_layer_desc *desc, const ssd
   return ctx->scope_end(scope, SSDT_BWD);
 #undef GET
 #undef HIP_IF
+}
+
+ssdt_status ssdt_sgd_update(ssdt_ctx *ctx, void *w, const void *g, size_t numel, int32_t dtype, float lr, ssdt_stream stream) {
+  if (!ctx) return SSDT_E_INVAL;
+  if (ctx->be->is_sim()) return ctx->fail(SSDT_E_UNSUPPORTED, "sgd_update: the simulated backend has no GPU");
+  if (!w || !g || (dtype != SSDT_F32 && dtype != SSDT_BF16)) return ctx->fail(SSDT_E_INVAL, "sgd_update: null pointer or unknown dtype");
+  hipError_t e = k::sgd_update(w, g, numel, lr, dtype, (hipStream_t)stream);
+  if (e != hipSuccess) return ctx->fail(SSDT_E_HIP, "sgd_update: %s", hipGetErrorString(e));
+  return SSDT_OK;
 }
 
 }  // extern "C"

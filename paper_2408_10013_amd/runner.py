@@ -58,6 +58,8 @@ class Layer:
         self.act, self.norm, self.mask, self.has_bias, self.eps = act, norm, mask, has_bias, eps
         self.desc = sb.make_desc(arch=arch, dtype=dtype, act=act, norm=norm, mask=mask, has_bias=has_bias, B=B, S=S,
                                  S_kv=S_kv, H=H, A=A, F=F, eps=eps)
+        self.desc_acc = sb.make_desc(arch=arch, dtype=dtype, act=act, norm=norm, mask=mask, has_bias=has_bias, B=B, S=S,
+                                     S_kv=S_kv, H=H, A=A, F=F, eps=eps, accumulate=True)
         self.desc_ckpt = sb.make_desc(arch=arch, dtype=dtype, act=act, norm=norm, mask=mask, has_bias=has_bias, B=B,
                                       S=S, S_kv=S_kv, H=H, A=A, F=F, eps=eps, checkpoint=True)
         self.shapes = weight_shapes(arch, norm, has_bias, H, F)
@@ -104,6 +106,7 @@ class Stack:
         # layerwise full recomputation (the comparison arm of Sec. 4.3): forward registers only each layer's
         # input, backward re-runs the layer's forward inside its backward scope
         self.recompute = False
+        self.mb_saved: Dict[int, list] = {}
 
     def close(self):
         if self.ctx:
@@ -132,11 +135,14 @@ class Stack:
 
     # -- one pass ----------------------------------------------------------------------------
     def forward(self, x: torch.Tensor, enc_x: Optional[torch.Tensor] = None, kv_len: Optional[torch.Tensor] = None,
-                offload=True):
+                offload=True, micro_batch: Optional[int] = None, keep_last: int = -1):
         """x: input of the first layer of the (decoder) stack; enc_x: input of the encoder stack for
         an encoder-decoder.  Returns the device pointer of the output (owned by the caller)."""
         ctx, L = self.ctx, len(self.layers)
-        sb.ssdt_step_begin(ctx, L)
+        if micro_batch is None:
+            sb.ssdt_step_begin(ctx, L)
+        else:   # the caller has begun the step; this pass belongs to one of its micro-batches
+            sb.ssdt_micro_batch(ctx, micro_batch, keep_last)
         self.kv_len = kv_len
         kvp = kv_len.data_ptr() if kv_len is not None else 0
         n_enc = sum(1 for l in self.layers if l.arch == "t5_enc") if enc_x is not None else 0
@@ -161,12 +167,19 @@ class Stack:
         y = run(n_enc, L, x, enc_ptr)
         if enc_ptr:
             sb.ssdt_arena_free(ctx, enc_ptr, self.stream)
+        if micro_batch is not None:
+            self.mb_saved[micro_batch] = [l.saved for l in self.layers]
         return y
 
-    def backward(self, dy: torch.Tensor, dx_out: Optional[torch.Tensor] = None):
+    def backward(self, dy: torch.Tensor, dx_out: Optional[torch.Tensor] = None, micro_batch: Optional[int] = None,
+                 accumulate: bool = False):
         """Runs backward through the stack; gradients land in each layer's .g; returns dx of the
         first (decoder) layer and, for an encoder-decoder, dx of the encoder input."""
         ctx, L = self.ctx, len(self.layers)
+        if micro_batch is not None:
+            sb.ssdt_micro_batch(ctx, micro_batch)
+            for l, sv in zip(self.layers, self.mb_saved.pop(micro_batch)):
+                l.saved = sv
         kvp = self.kv_len.data_ptr() if self.kv_len is not None else 0
         n_enc = self.n_enc
         bufs = [torch.empty_like(dy), torch.empty_like(dy)]
@@ -198,8 +211,8 @@ class Stack:
                     y2, l.saved = sb.ssdt_layer_fwd(ctx, l.desc, l.wstruct, i, ins[0], ins[1], kvp, self.ws_ptr,
                                                     self.ws_bytes, self.stream)
                     sb.ssdt_arena_free(ctx, y2, self.stream)
-                sb.ssdt_layer_bwd(ctx, l.desc, l.wstruct, l.saved, kvp, cur.data_ptr(), out.data_ptr(), denc_ptr,
-                                  l.gstruct, self.ws_ptr, self.ws_bytes, self.stream)
+                sb.ssdt_layer_bwd(ctx, l.desc_acc if accumulate else l.desc, l.wstruct, l.saved, kvp, cur.data_ptr(),
+                                  out.data_ptr(), denc_ptr, l.gstruct, self.ws_ptr, self.ws_bytes, self.stream)
                 if self.recompute:
                     sb.ssdt_scope_end(ctx, i, sb.BWD)
                 sb.ssdt_release(ctx, i, self.stream)
@@ -211,6 +224,32 @@ class Stack:
             dx_enc = run(n_enc, 0, d_enc, 0)
             return dx, dx_enc
         return dx, None
+
+    def train_step(self, xs: List[torch.Tensor], dys: List[torch.Tensor], lr: float, in_flight: int = 1):
+        """One training step with gradient accumulation over the micro-batches xs[i] (dys[i] stands for the loss
+        gradient) followed by a plain SGD update of every parameter (Sec. 1, Sec. 4.1).  in_flight = 1 runs forward
+        and backward of each micro-batch back to back; in_flight = 2 runs two forwards before their backwards
+        (newest first), which needs the cache's per-micro-batch records (Sec. 3.1).  Returns the outputs' pointers'
+        contents as tensors (cloned) for checking."""
+        ctx, L = self.ctx, len(self.layers)
+        sb.ssdt_step_begin(ctx, L)
+        ys, first = [], True
+        for g0 in range(0, len(xs), in_flight):
+            group = list(range(g0, min(g0 + in_flight, len(xs))))
+            outs = {}
+            for mb in group:
+                # only the micro-batch whose backward follows at once keeps its last layer on the device
+                outs[mb] = self.forward(xs[mb], micro_batch=mb, keep_last=-1 if mb == group[-1] else 0)
+            for mb in reversed(group):
+                ys.append((mb, self.view(outs[mb], tuple(xs[mb].shape)).clone()))
+                self.backward(dys[mb], micro_batch=mb, accumulate=not first)
+                sb.ssdt_arena_free(ctx, outs[mb], self.stream)
+                first = False
+        dt = sb.F32 if self.dtype == "f32" else sb.BF16
+        for l in self.layers:
+            for k, w in l.w.items():
+                sb.ssdt_sgd_update(ctx, w.data_ptr(), l.g[k].data_ptr(), w.numel(), dt, lr, self.stream)
+        return [y for _, y in sorted(ys, key=lambda t: t[0])]
 
     def stats(self):
         return sb.ssdt_get_stats(self.ctx)
