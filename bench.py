@@ -119,6 +119,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sweep", default="", help="comma-separated micro-batch sizes: one off/budget measurement per size "
                                                 "(throughput and activation memory vs micro-batch), printed as one JSON line")
+    ap.add_argument("--accumulate-sweep", default="",
+                    help="comma-separated micro-batch sizes: a training step of --global-batch sequences split into "
+                         "micro-batches of each size, gradients accumulated, one SGD update at the end (no offload)")
+    ap.add_argument("--global-batch", type=int, default=16)
     ap.add_argument("--copy-probe", action="store_true",
                     help="run one 1 GiB device-to-device copy and exit: the kernel of known size that calibrates the "
                          "HBM byte counters of a profiler run")
@@ -150,10 +154,8 @@ def main():
     tdt = torch.float32 if dtype == "f32" else torch.bfloat16
     weights_cache = {}
 
-    def measure(B, want):
-        layers = runner.layers_from_config(cfg, B=B, n_layers=args.layers or None)
-        L = len(layers)
-        # seeded synthetic weights and inputs, generated on the device (weights are the same for every B)
+    def init_weights(layers):
+        """Seeded synthetic weights, generated on the device (the same for every micro-batch size)."""
         gen = torch.Generator(device=dev)
         gen.manual_seed(synth.BASE_SEED + cfg["index"])
         for li, l in enumerate(layers):
@@ -168,6 +170,12 @@ def main():
                         w[name] = torch.zeros(shp, device=dev, dtype=tdt)
                 weights_cache[li] = w
             l.set_weights(weights_cache[li])
+        return gen
+
+    def measure(B, want):
+        layers = runner.layers_from_config(cfg, B=B, n_layers=args.layers or None)
+        L = len(layers)
+        gen = init_weights(layers)
         first_dec = next((l for l in layers if l.arch != "t5_enc"), layers[0])
         x = torch.randn(first_dec.T, first_dec.H, generator=gen, device=dev, dtype=torch.float32).to(tdt)
         dy = torch.randn(first_dec.T, first_dec.H, generator=gen, device=dev, dtype=torch.float32).to(tdt)
@@ -257,6 +265,50 @@ def main():
             m["exposed_io_pct"] = max(0.0, (m["ms_per_step"] - modes["off"]["ms_per_step"]) / m["ms_per_step"] * 100.0)
             m["arena_peak_vs_off"] = m["arena_peak_bytes"] / max(1, modes["off"]["arena_peak_bytes"])
         return layers, modes, prof, setup
+
+    def measure_accumulate(B, n_mb):
+        """Training step of n_mb micro-batches of size B with gradient accumulation and one SGD update; everything
+        stays on the device (budget 0).  Returns time per step, algorithmic rate, time in the SGD kernel."""
+        layers = runner.layers_from_config(cfg, B=B, n_layers=args.layers or None)
+        gen = init_weights(layers)
+        T, H = layers[0].T, layers[0].H
+        xs = [torch.randn(T, H, generator=gen, device=dev, dtype=torch.float32).to(tdt) for _ in range(min(n_mb, 2))]
+        dys = [torch.randn(T, H, generator=gen, device=dev, dtype=torch.float32).to(tdt) * 1e-3 for _ in range(min(n_mb, 2))]
+        xs = [xs[i % len(xs)] for i in range(n_mb)]
+        dys = [dys[i % len(dys)] for i in range(n_mb)]
+        per_layer = [runner.saved_bytes_per_layer(l) for l in layers]
+        st = runner.Stack(layers, sum(per_layer) + max(per_layer) + (64 << 20), 0, "cuda:0", keep_last=1,
+                          min_offload_elems=1 << 20, budget_bytes=0)
+        st.register_weights()
+        for _ in range(args.warmup):
+            st.train_step(xs, dys, 1e-6)
+        torch.cuda.synchronize()
+        sb.ssdt_profile(st.ctx, True)
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            st.train_step(xs, dys, 1e-6)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / args.steps
+        prof = {p["name"]: p for p in sb.ssdt_profile_read(st.ctx)}
+        sb.ssdt_profile(st.ctx, False)
+        peak = st.stats()["arena_peak_in_use"]
+        st.close()
+        del st, layers
+        torch.cuda.empty_cache()
+        fl = n_mb * stack_flops(runner.layers_from_config(cfg, B=B, n_layers=args.layers or None))
+        upd = next((v["ms"] for k, v in prof.items() if "add" in k or "sgd" in k), 0.0) / args.steps
+        gemm = next((v for k, v in prof.items() if k.startswith("gemm_nt256")), None)
+        return {"micro_batch": B, "micro_batches": n_mb, "ms_per_step": dt * 1e3, "tflops": fl / dt / 1e12,
+                "sgd_update_ms": upd, "activation_peak_bytes": peak,
+                "gemm_tflops": gemm["flops"] / (gemm["ms"] * 1e-3) / 1e12 if gemm else None}
+
+    if args.accumulate_sweep:
+        rows = [measure_accumulate(B, max(1, args.global_batch // B)) for B in [int(v) for v in args.accumulate_sweep.split(",")]]
+        print(json.dumps({"metric": "training-step TFLOP/s vs micro-batch size at a fixed global batch "
+                                    "(gradient accumulation + SGD update, no offload)", "unit": "TFLOP/s",
+                          "workload": args.workload, "global_batch": args.global_batch, "steps": args.steps,
+                          "warmup": args.warmup, "dtype": dtype, "data": "synthetic", "sweep": rows}))
+        return
 
     link = link_rate(torch, dev)
     if args.sweep:
