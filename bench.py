@@ -73,7 +73,7 @@ def cpu_baseline(cfg, seconds_hint=20.0):
     from oracle import layer_oracle as lo
     from paper_2408_10013_amd import synth
     arch = cfg["stack"][0][0]
-    B, S = 1, 1024   # about 10-20 s of host work at the headline widths
+    B, S = 1, 2048   # about 10-20 s of host work at the headline widths
     d = lo.LayerDesc(arch=arch, B=B, S=S, H=cfg["H"], A=cfg["A"], F=cfg["F"], act=cfg["act"], norm=cfg["norm"],
                      mask="causal" if cfg["mask"] == "causal" else "none", has_bias=cfg["has_bias"], eps=cfg["eps"])
     shapes = lo.weight_shapes(d)
