@@ -528,3 +528,78 @@ def test_records_per_micro_batch_match_checker():
     sb.ssdt_scope_end(ctx, 0)
     sb.ssdt_step_begin(ctx, L)
     sb.ssdt_ctx_destroy(ctx)
+
+
+def test_random_traces_match_checker_and_reload_bit_exactly():
+    """Seeded random sequences of scopes, saves (views, repeats, weights, small tensors), budgets, kept layers and
+    micro-batches, with stores and loads completing in random amounts: bookkeeping equals the checker's record by
+    record, no two live arena blocks overlap, and every tensor fetched in backward holds the bytes it was saved
+    with."""
+    rng = np.random.default_rng(20240810)
+    for trial in range(40):
+        L = int(rng.integers(1, 5))
+        n_mb = int(rng.integers(1, 3))
+        kw = dict(min_offload_elems=int(rng.choice([0, 64, 1 << 20])), keep_last=int(rng.integers(0, 2)),
+                  budget_bytes=int(rng.choice([-1, 0, 3000, 20000])))
+        pool = int(rng.choice([1 << 12, 1 << 16, 1 << 20]))
+        ctx, ar = make(arena_bytes=1 << 20, pool_bytes=pool, **kw)
+        sb.ssdt_step_begin(ctx, L)
+        reg = ro.RegistryOracle(L, kw["min_offload_elems"], None if kw["budget_bytes"] < 0 else kw["budget_bytes"],
+                                kw["keep_last"], pool)
+        wbuf = np.zeros(4096, dtype=np.uint8)
+        sb.ssdt_register_weight(ctx, wbuf.ctypes.data, 4096); reg.register_weight("W")
+        live = {}                                   # (mb, layer, name) -> (tid, ptr, bytes, fill)
+        for mb in range(n_mb):
+            klo = int(rng.integers(-1, 2))
+            sb.ssdt_micro_batch(ctx, mb, klo); reg.micro_batch(mb, None if klo < 0 else klo)
+            for l in range(L):
+                sb.ssdt_scope_begin(ctx, l); reg.scope_begin(l)
+                mine = {}
+                for s_i in range(int(rng.integers(1, 7))):
+                    kind = rng.integers(0, 10)
+                    if kind == 0:                   # a weight: bypassed
+                        assert sb.ssdt_save(ctx, wbuf.ctypes.data, 4096, 0, [1024], sb.F32) == 0
+                        assert reg.save("W", 4096, 1024) == 0
+                        continue
+                    if kind <= 2 and mine:          # another view of a storage saved before
+                        name = list(mine)[int(rng.integers(0, len(mine)))]
+                    else:
+                        name = "t%d" % s_i
+                        nbytes = int(rng.choice([64, 256, 1000, 4096, 10000]))
+                        p = sb.ssdt_arena_alloc(ctx, nbytes)
+                        fill = int(rng.integers(1, 255))
+                        ar.view(p, nbytes)[:] = fill
+                        mine[name] = (p, nbytes, fill)
+                    p, nbytes, fill = mine[name]
+                    numel = int(rng.integers(1, nbytes // 4 + 1))
+                    got = sb.ssdt_save(ctx, p, nbytes, 0, [numel], sb.F32)
+                    assert got == reg.save((mb, l, name), nbytes, numel)
+                    live[(mb, l, name)] = (got, p, nbytes, fill)
+                sb.ssdt_scope_end(ctx, l); reg.scope_end(l)
+                sb.ssdt_offload(ctx, l)
+                for p, _, _ in mine.values():
+                    sb.ssdt_arena_free(ctx, p)
+                sb.ssdt_sim_complete(ctx, 0, int(rng.integers(0, 4)))
+        compare(ctx, reg)
+        recs = records(ctx)
+        spans = sorted((r["device_ptr"], r["bytes"]) for r in recs if r["device_ptr"])
+        for (a, na), (b, _) in zip(spans, spans[1:]):
+            assert a + na <= b, "live arena blocks overlap"
+        sb.ssdt_sim_complete(ctx, 0, int(rng.choice([0, 1, 2, 50])))   # some stores are still in flight: forwarding
+        for mb in reversed(range(n_mb)):
+            sb.ssdt_micro_batch(ctx, mb)
+            for l in reversed(range(L)):
+                if rng.integers(0, 2):
+                    sb.ssdt_prefetch(ctx, l)
+                sb.ssdt_sim_complete(ctx, 1, int(rng.integers(0, 3)))
+                for (m2, l2, name), (tid, p, nbytes, fill) in live.items():
+                    if (m2, l2) != (mb, l):
+                        continue
+                    q = sb.ssdt_get(ctx, tid) if tid else p      # bypassed tensors stay where they were
+                    assert bytes(ar.view(q, nbytes)) == bytes([fill]) * nbytes, (trial, mb, l, name)
+                sb.ssdt_release(ctx, l)
+        st = sb.ssdt_get_stats(ctx)
+        assert st["arena_in_use"] == 0 and st["released"] == st["unique"], (trial, st)
+        assert st["loads"] + st["forwarded"] <= st["offloaded"] + st["demand_loads"]
+        sb.ssdt_step_begin(ctx, L)
+        sb.ssdt_ctx_destroy(ctx)
