@@ -46,6 +46,7 @@ struct Gemm {
 hipError_t gemm(const Gemm &g, hipStream_t s);
 hipError_t gemm_generic(const Gemm &g, hipStream_t s);  // the FMA kernel, any shape (gemm() falls back to it)
 extern int g_force_waves;                               // 0 = choose; > 0 pins the tile rows per workgroup-order group
+extern int g_attn_kb;                                   // 0 = choose; 1 pins the register-staged key-side attention backward
 extern int g_force_tile;                                // 0 = choose; 128 / 256 pin the matrix-core tile
 // scratch bytes gemm() can make use of for this problem (0 for fp32)
 size_t gemm_scratch_bytes(int M, int N, int K, bool transA, bool transB, int dtype);

@@ -382,6 +382,179 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dkv_k(FaP p) {
 }
 
 // ------------------------------------------------------------------------------------------
+// backward, key side, head size 128: same arithmetic as fa_bwd_dkv_k, organised around what bounds it.
+// Timing variants of that kernel showed the un-prefetched Q / dO tile loads (with their barriers) to be 40 % of
+// its time, and prefetching through registers does not fit beside the 128 accumulator registers at two
+// wavefronts per SIMD.  Here the tiles are 32 queries, double-buffered in LDS and filled by direct
+// global-to-LDS loads issued one tile ahead (no registers), V rows live in LDS, and rows are unpadded 256-byte
+// lines whose 16-byte chunk index is XOR-ed with (row & 15) so that both the row-fragment reads and the
+// transposing reads are free of bank conflicts.  The two tile buffers are separate arrays and the loop is
+// unrolled by two, so that the compiler can see that a load in flight never targets the buffer being read.
+// ------------------------------------------------------------------------------------------
+typedef __attribute__((address_space(3))) void lds_void_t;
+
+// element offset of 16-byte chunk c of row r in a swizzled tile with 128-element rows
+__device__ __forceinline__ int sw128(int r, int c) { return r * 128 + ((c ^ (r & 15)) << 3); }
+
+// ROWS x 128 bf16 from global rows (stride ld) into a swizzled LDS tile by direct loads: one wavefront
+// instruction moves four rows; wavefront w of four takes rows 16 j + 4 w .. + 3 of every group of 16
+// (g is uniform over the wavefront; the per-lane part of the address is a 32-bit element offset, so the loads can
+// take a scalar base and cost one address register each)
+template <int ROWS>
+__device__ __forceinline__ void dma_tile128(const uint16_t *g, int ld, uint16_t *s, int w, int lane) {
+  asm volatile("" : "+v"(lane));  // offsets are recomputed at every use instead of living in (spilled) registers
+#pragma unroll
+  for (int j = 0; j < ROWS / 16; ++j) {
+    const int r0 = j * 16 + w * 4, r = r0 + (lane >> 4), c = lane & 15;
+    const unsigned off = (unsigned)(r * ld + ((c ^ (r & 15)) << 3));
+    __builtin_amdgcn_global_load_lds(g + off, (lds_void_t *)(s + r0 * 128), 16, 0, 0);
+  }
+}
+
+// one 32-query tile against this wavefront's 32 keys.  Swizzled offsets are XORs of a per-lane base with a
+// constant; the bases are re-derived per call (the empty asm keeps the compiler from hoisting the dozens of
+// derived addresses out of the tile loop and spilling them).
+__device__ __forceinline__ void dkv128_tile(const FaP &p, const uint16_t *sQ, const uint16_t *sdO, const uint16_t *sV,
+                                            const float *sLse, const float *sDelta, const bf16x8_t (&kf)[8],
+                                            f32x16_t (&dkacc)[4], f32x16_t (&dvacc)[4], int i0, int k0, int limit,
+                                            int w, int lane) {
+  const int half = lane >> 5, li = lane & 31, kj = k0 + li;
+  if (p.mask == SSDT_MASK_CAUSAL && i0 + 31 < k0) return;  // every query of the tile precedes this wavefront's keys
+  const bool need_mask = (p.mask == SSDT_MASK_CAUSAL && i0 < k0 + 31) || (k0 + 32 > limit);
+  const float sc = p.scale * kLog2e;
+  // row fragments: row li, chunk (2 ks + half) ^ (li & 15)  ->  base ^ (ks << 4) elements
+  int rbase = li * 128 + (((half ^ li) & 1) << 3) + (((li & 15) >> 1) << 4);
+  asm volatile("" : "+v"(rbase));
+  const int vbase = rbase + w * 32 * 128;
+  f32x16_t sacc, dpacc;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) { sacc[r] = 0.f; dpacc[r] = 0.f; }
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) {
+    const bf16x8_t qa = *(const bf16x8_t *)(sQ + (rbase ^ (ks << 4)));
+    const bf16x8_t da = *(const bf16x8_t *)(sdO + (rbase ^ (ks << 4)));
+    const bf16x8_t vv = *(const bf16x8_t *)(sV + (vbase ^ (ks << 4)));
+    sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kf[ks], sacc, 0, 0, 0);
+    dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(da, vv, dpacc, 0, 0, 0);
+    if (ks & 1) __builtin_amdgcn_sched_barrier(0);  // at most two steps' fragments in flight: registers are short
+  }
+  // this lane: key kj, queries i0 + g*8 + half*4 + 0..3
+  float pv[16], dsv[16];
+#pragma unroll
+  for (int g = 0; g < 4; ++g) {
+    const int qo = g * 8 + half * 4;
+    const float4 l4 = *(const float4 *)(sLse + qo), d4 = *(const float4 *)(sDelta + qo);
+    const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dv[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int r = g * 4 + e;
+      float pe = __builtin_amdgcn_exp2f(sacc[r] * sc - lv[e] * kLog2e);
+      bool dead = lv[e] == -INFINITY;
+      if (need_mask) dead = dead || kj >= limit || (p.mask == SSDT_MASK_CAUSAL && kj > i0 + qo + e);
+      pe = dead ? 0.f : pe;
+      pv[r] = pe;
+      dsv[r] = pe * (dpacc[r] - dv[e]);
+    }
+  }
+  // transposing reads (see frag_tr): lane L of a group of 16 supplies the 4 elements at k-row (k + L/4), columns
+  // c0 + 4 (L % 4) ..., and receives column c0 + L, k-rows k .. k+3.  k-rows used: 16 gs + 4 half (+ 8) + L/4;
+  // the swizzle term of such a row is 4 half (+ 8) + L/4, so the offset for column block d is base ^ (d << 5).
+  const int L = lane & 15, kr = L >> 2, g1 = (lane >> 4) & 1, lowc = g1 * 2 + ((L & 3) >> 1);
+  int t0 = (half * 4 + kr) * 128 + ((lowc ^ (half * 4 + kr)) << 3) + (L & 1) * 4;
+  int t1 = (half * 4 + 8 + kr) * 128 + ((lowc ^ (half * 4 + 8 + kr)) << 3) + (L & 1) * 4;
+  asm volatile("" : "+v"(t0), "+v"(t1));
+#pragma unroll
+  for (int gs = 0; gs < 2; ++gs) {
+    const bf16x8_t pf = pack8(pv + gs * 8, pv + gs * 8 + 4), dsf = pack8(dsv + gs * 8, dsv + gs * 8 + 4);
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+      const int o0 = (t0 ^ (d << 5)) + gs * 2048, o1 = (t1 ^ (d << 5)) + gs * 2048;
+      union { struct { s16x4_t a, b; } s; bf16x8_t v; } dot, qt;
+      dot.s.a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)(sdO + o0));
+      dot.s.b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)(sdO + o1));
+      dvacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dot.v, pf, dvacc[d], 0, 0, 0);
+      qt.s.a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)(sQ + o0));
+      qt.s.b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)(sQ + o1));
+      dkacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qt.v, dsf, dkacc[d], 0, 0, 0);
+      if (d & 1) __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+}
+
+__global__ __launch_bounds__(256, 2) void fa_bwd_dkv128_k(FaP p) {
+  constexpr int D = 128, BQ = 32;
+  __shared__ __attribute__((aligned(1024))) uint16_t sV[128 * D];
+  __shared__ __attribute__((aligned(1024))) uint16_t sQ0[BQ * D], sdO0[BQ * D], sQ1[BQ * D], sdO1[BQ * D];
+  __shared__ __attribute__((aligned(16))) float sLse0[BQ], sDelta0[BQ], sLse1[BQ], sDelta1[BQ];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, half = lane >> 5, li = lane & 31;
+  const int h = blockIdx.y, b = blockIdx.z;
+  const int kblock = blockIdx.x * 128, k0 = kblock + w * 32, kj = k0 + li;
+  int limit = p.Sk;
+  if (p.mask == SSDT_MASK_KEYPAD) limit = min(limit, max(0, p.kv_len[b]));
+  const uint16_t *kp = p.k + (long)(b * p.Sk + kj) * p.ldk + h * D;
+  bf16x8_t kf[8];
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) kf[ks] = *(const bf16x8_t *)(kp + ks * 16 + half * 8);
+  f32x16_t dkacc[4], dvacc[4];
+#pragma unroll
+  for (int d = 0; d < 4; ++d)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { dkacc[d][r] = 0.f; dvacc[d][r] = 0.f; }
+  const uint16_t *qg = p.q + (long)b * p.Sq * p.ldq + h * D, *dog = p.dout + (long)b * p.Sq * p.lddo + h * D;
+  const float *lse_g = p.lse + ((long)b * p.A + h) * p.Sq, *delta_g = p.delta + ((long)b * p.A + h) * p.Sq;
+  const int nt = p.Sq / BQ;
+  const int tstart = kblock < limit ? (p.mask == SSDT_MASK_CAUSAL ? kblock / BQ : 0) : nt;
+
+  if (tstart < nt) {
+    dma_tile128<128>(p.v + (long)(b * p.Sk + kblock) * p.ldv + h * D, (int)p.ldv, sV, w, lane);
+    dma_tile128<BQ>(qg + (long)tstart * BQ * p.ldq, (int)p.ldq, sQ0, w, lane);
+    dma_tile128<BQ>(dog + (long)tstart * BQ * p.lddo, (int)p.lddo, sdO0, w, lane);
+    if (tid < BQ) sLse0[tid] = lse_g[tstart * BQ + tid];
+    else if (tid < 2 * BQ) sDelta0[tid - BQ] = delta_g[tstart * BQ + tid - BQ];
+  }
+  // tile t sits in buffer (t - tstart) & 1; while it is consumed, tile t+1 loads into the other buffer
+  for (int t = tstart; t < nt; t += 2) {
+    __builtin_amdgcn_s_waitcnt(0xF70);  // vmcnt(0): this wavefront's loads of tile t have landed
+    __syncthreads();                    // everyone's have, and everyone is done with the other buffer
+    float rstat = 0.f;
+    if (t + 1 < nt) {
+      dma_tile128<BQ>(qg + (long)(t + 1) * BQ * p.ldq, (int)p.ldq, sQ1, w, lane);
+      dma_tile128<BQ>(dog + (long)(t + 1) * BQ * p.lddo, (int)p.lddo, sdO1, w, lane);
+      if (tid < BQ) rstat = lse_g[(t + 1) * BQ + tid];
+      else if (tid < 2 * BQ) rstat = delta_g[(t + 1) * BQ + tid - BQ];
+    }
+    dkv128_tile(p, sQ0, sdO0, sV, sLse0, sDelta0, kf, dkacc, dvacc, t * BQ, k0, limit, w, lane);
+    if (t + 1 >= nt) break;
+    if (tid < BQ) sLse1[tid] = rstat;
+    else if (tid < 2 * BQ) sDelta1[tid - BQ] = rstat;
+    __builtin_amdgcn_s_waitcnt(0xF70);
+    __syncthreads();
+    if (t + 2 < nt) {
+      dma_tile128<BQ>(qg + (long)(t + 2) * BQ * p.ldq, (int)p.ldq, sQ0, w, lane);
+      dma_tile128<BQ>(dog + (long)(t + 2) * BQ * p.lddo, (int)p.lddo, sdO0, w, lane);
+      if (tid < BQ) rstat = lse_g[(t + 2) * BQ + tid];
+      else if (tid < 2 * BQ) rstat = delta_g[(t + 2) * BQ + tid - BQ];
+    }
+    dkv128_tile(p, sQ1, sdO1, sV, sLse1, sDelta1, kf, dkacc, dvacc, (t + 1) * BQ, k0, limit, w, lane);
+    if (t + 2 < nt) {
+      if (tid < BQ) sLse0[tid] = rstat;
+      else if (tid < 2 * BQ) sDelta0[tid - BQ] = rstat;
+    }
+  }
+  uint16_t *dkp = p.dk + (long)(b * p.Sk + kj) * p.lddk + h * D, *dvp = p.dv + (long)(b * p.Sk + kj) * p.lddv + h * D;
+#pragma unroll
+  for (int d = 0; d < 4; ++d)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int o = d * 32 + g * 8 + half * 4;
+      *(uint2 *)(dkp + o) = make_uint2(pack_bf2(dkacc[d][g * 4 + 0] * p.scale, dkacc[d][g * 4 + 1] * p.scale),
+                                       pack_bf2(dkacc[d][g * 4 + 2] * p.scale, dkacc[d][g * 4 + 3] * p.scale));
+      *(uint2 *)(dvp + o) = make_uint2(pack_bf2(dvacc[d][g * 4 + 0], dvacc[d][g * 4 + 1]),
+                                       pack_bf2(dvacc[d][g * 4 + 2], dvacc[d][g * 4 + 3]));
+    }
+}
+
+// ------------------------------------------------------------------------------------------
 // backward, query side: one workgroup = 128 queries, each wavefront 32; loops over 64-key tiles.
 // dQ[i] = scale sum_j dS_ij k_j, accumulated in registers in a fixed order (no atomics).
 // ------------------------------------------------------------------------------------------
@@ -481,6 +654,8 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dq_k(FaP p) {
                      pack_bf2(dqacc[d][g * 4 + 2] * p.scale, dqacc[d][g * 4 + 3] * p.scale));
 }
 
+int g_attn_kb = 0;  // test hook: 1 pins the register-staged key-side kernel
+
 hipError_t attn_bwd_mfma_bf16(const Attn &a, hipStream_t s) {
   if (!fa_supported(a)) return hipErrorNotSupported;
   if (a.mask == SSDT_MASK_CAUSAL && a.Sq != a.Sk) return hipErrorNotSupported;
@@ -495,7 +670,10 @@ hipError_t attn_bwd_mfma_bf16(const Attn &a, hipStream_t s) {
   FaP p = to_fa(a);
   dim3 gk(a.Sk / 128, a.A, a.B), gq(a.Sq / 128, a.A, a.B);
   if (a.d == 128) {
-    hipLaunchKernelGGL(fa_bwd_dkv_k<128>, gk, dim3(256), 0, s, p);
+    const bool dma = (((uintptr_t)a.q | (uintptr_t)a.v | (uintptr_t)a.dout) & 15) == 0 && a.ldq % 8 == 0 && a.ldv % 8 == 0 &&
+                     g_attn_kb != 1;
+    if (dma) hipLaunchKernelGGL(fa_bwd_dkv128_k, gk, dim3(256), 0, s, p);
+    else hipLaunchKernelGGL(fa_bwd_dkv_k<128>, gk, dim3(256), 0, s, p);
     hipLaunchKernelGGL(fa_bwd_dq_k<128>, gq, dim3(256), 0, s, p);
   } else {
     hipLaunchKernelGGL(fa_bwd_dkv_k<64>, gk, dim3(256), 0, s, p);
