@@ -11,6 +11,7 @@ namespace {
 class HipBackend : public Backend {
  public:
   hipStream_t q_[2] = {nullptr, nullptr};
+  hipStream_t aux_ = nullptr;  // side stream for bandwidth-bound kernels that overlap the caller's GEMMs (default priority)
   void *pool_ = nullptr;
   std::vector<Ev *> free_[2];  // [timing]
   std::vector<Ev *> all_;
@@ -29,6 +30,7 @@ class HipBackend : public Backend {
     }
     for (int d = 0; d < 2; ++d)
       if (!check(hipStreamCreateWithFlags(&q_[d], hipStreamNonBlocking), "hipStreamCreateWithFlags")) return false;
+    if (!check(hipStreamCreateWithFlags(&aux_, hipStreamNonBlocking), "hipStreamCreateWithFlags")) return false;
     if (pool_bytes && !check(hipHostMalloc(&pool_, pool_bytes, hipHostMallocDefault), "hipHostMalloc(pool)")) return false;
     return true;
   }
@@ -39,6 +41,7 @@ class HipBackend : public Backend {
     }
     for (int d = 0; d < 2; ++d)
       if (q_[d]) (void)hipStreamDestroy(q_[d]);
+    if (aux_) (void)hipStreamDestroy(aux_);
     if (pool_) (void)hipHostFree(pool_);
   }
   bool is_sim() const override { return false; }
@@ -78,6 +81,7 @@ class HipBackend : public Backend {
   }
   void wait_queue(int dir, Ev *e) override { wait(q_[dir], e); }
   ssdt_stream queue_stream(int dir) override { return q_[dir]; }
+  ssdt_stream aux_stream() override { return aux_; }
   void recycle(Ev *e) override { free_[e->timing ? 1 : 0].push_back(e); }
   double elapsed_ms(Ev *a, Ev *b) override {
     float ms = 0;

@@ -45,6 +45,7 @@ class Backend {
   virtual Ev *copy(int dir, void *dst, const void *src, size_t n, Ev *after) = 0;
   virtual void wait_queue(int dir, Ev *e) = 0;                    // a copy queue waits for e
   virtual ssdt_stream queue_stream(int dir) = 0;                  // identity of a copy queue as a stream
+  virtual ssdt_stream aux_stream() { return nullptr; }            // side stream for kernels that may overlap the caller's; null if none
   virtual void recycle(Ev *e) = 0;
   virtual double elapsed_ms(Ev *a, Ev *b) = 0;
   virtual void sync_io() = 0;

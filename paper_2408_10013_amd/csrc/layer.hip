@@ -73,7 +73,7 @@ size_t bwd_scratch(const Dims &D) {
 
 struct BwdBufs {
   void *dh1, *t0, *t1, *t2, *dqkv, *dkvx, *denc, *scratch;
-  float *partial, *delta;
+  float *partial, *partial_side, *delta;
   size_t scratch_bytes;
 };
 void bwd_layout(const Dims &D, Ws &w, BwdBufs *b) {
@@ -85,6 +85,7 @@ void bwd_layout(const Dims &D, Ws &w, BwdBufs *b) {
   b->denc = D.dec ? w.take((size_t)D.Te * D.H * D.e) : nullptr;
   size_t rows = std::max(D.T, D.Te), cols = max3(3 * (size_t)D.H, D.F, 0);
   b->partial = (float *)w.take(k::colreduce_partial_floats((int)rows, (int)cols) * 4);
+  b->partial_side = (float *)w.take(k::colreduce_partial_floats((int)rows, (int)cols) * 4);
   b->delta = (float *)w.take((size_t)D.B * D.A * D.S * 4);
   b->scratch_bytes = bwd_scratch(D);
   b->scratch = b->scratch_bytes ? w.take(b->scratch_bytes) : nullptr;
@@ -363,11 +364,49 @@ ssdt_status ssdt_layer_bwd(ssdt_ctx *ctx, const ssdt_layer_desc *desc, const ssd
   // gradients of y = in W + b given dY: dW = in^T dY, db = column sums of dY
   // (with gradient accumulation the product is added to what dW holds: the residual epilogue reading dW itself)
   const bool accum = desc->accumulate != 0;
+  // The weight-gradient GEMM wants both operands with the token dimension contiguous, i.e. transposed copies.
+  // Those copies and the bias-gradient column sums are bandwidth-bound and independent of the input-gradient GEMM
+  // that follows, so for the matrix-core path they run on the context's side stream underneath that GEMM:
+  // wgrad() enqueues them there (after an event that says dY is ready) and remembers the GEMM; wgrad_flush(),
+  // called after the input-gradient GEMM has been enqueued, makes the caller's stream wait for the copies and
+  // enqueues the weight-gradient GEMM.  The side stream's next round starts only after an event recorded behind that
+  // GEMM on the caller's stream (a later dY depends on it in stream order anyway), so one scratch area suffices.
+  hipStream_t side = (hipStream_t)ctx->be->aux_stream();
+  struct Pending { bool on = false; int Kin, Nout, rows; void *dW; const uint16_t *At, *Bt; Ev *ready; } pend;
+  auto wgrad_flush = [&]() -> hipError_t {
+    if (!pend.on) return hipSuccess;
+    pend.on = false;
+    ctx->be->wait(stream, pend.ready);
+    drop(ctx->be.get(), pend.ready);
+    k::Gemm g;
+    g.M = pend.Kin; g.N = pend.Nout; g.K = pend.rows; g.A = pend.At; g.lda = pend.rows; g.transA = false; g.B = pend.Bt;
+    g.ldb = pend.rows; g.transB = true; g.C = pend.dW; g.ldc = pend.Nout; g.epi = accum ? k::EPI_BIAS_RESID : k::EPI_NONE;
+    g.resid = accum ? pend.dW : nullptr; g.ldr = pend.Nout; g.act = desc->act; g.dtype = dt;
+    return k::gemm(g, st);
+  };
   auto wgrad = [&](const void *in, int Kin, const void *dY, int Nout, int rows, void *dW, void *db) -> hipError_t {
-    hipError_t e1 = mm(Kin, Nout, rows, in, Kin, true, dY, Nout, false, dW, accum ? k::EPI_BIAS_RESID : k::EPI_NONE,
-                       accum ? dW : nullptr, nullptr);
+    const size_t a_bytes = ((size_t)Kin * rows * 2 + 255) / 256 * 256, b_bytes = (size_t)Nout * rows * 2;
+    const bool overlap = side && dt == SSDT_BF16 && Kin % 128 == 0 && Nout % 128 == 0 && rows % 64 == 0 &&
+                         a_bytes + b_bytes <= bf.scratch_bytes;
+    if (!overlap) {
+      hipError_t e1 = mm(Kin, Nout, rows, in, Kin, true, dY, Nout, false, dW, accum ? k::EPI_BIAS_RESID : k::EPI_NONE,
+                         accum ? dW : nullptr, nullptr);
+      if (e1 != hipSuccess) return e1;
+      if (db) return k::colsum(dY, Nout, db, bf.partial, rows, Nout, dt, accum, st);
+      return hipSuccess;
+    }
+    hipError_t e0 = wgrad_flush();  // at most one round is in flight
+    if (e0 != hipSuccess) return e0;
+    Ev *go = hold(ctx->be->record(stream, false));  // dY (and everything before it) is ready
+    ctx->be->wait(side, go);
+    drop(ctx->be.get(), go);
+    uint16_t *At = (uint16_t *)bf.scratch, *Bt = (uint16_t *)((char *)bf.scratch + a_bytes);
+    hipError_t e1 = k::transpose(in, Kin, At, rows, rows, Kin, SSDT_BF16, side);     // [rows, Kin] -> [Kin, rows]
+    if (e1 == hipSuccess) e1 = k::transpose(dY, Nout, Bt, rows, rows, Nout, SSDT_BF16, side);  // [rows, Nout] -> [Nout, rows]
+    if (e1 == hipSuccess && db) e1 = k::colsum(dY, Nout, db, bf.partial_side, rows, Nout, dt, accum, side);
     if (e1 != hipSuccess) return e1;
-    if (db) return k::colsum(dY, Nout, db, bf.partial, rows, Nout, dt, accum, st);
+    pend.on = true; pend.Kin = Kin; pend.Nout = Nout; pend.rows = rows; pend.dW = dW; pend.At = At; pend.Bt = Bt;
+    pend.ready = hold(ctx->be->record(side, false));
     return hipSuccess;
   };
   auto nbwd = [&](const void *dout, const void *xin, const void *mean, const void *rstd, const void *gamma,
@@ -403,11 +442,13 @@ ssdt_status ssdt_layer_bwd(ssdt_ctx *ctx, const ssdt_layer_desc *desc, const ssd
     const void *aux = g;
     if (D.gelu) { GET(SSDT_SV_H1, h1); aux = h1; }
     HIP_IF(mm(D.T, D.F, D.H, dr2, D.H, false, w->w_2, D.H, true, bf.dh1, k::EPI_ACTBWD, nullptr, aux));
+    HIP_IF(wgrad_flush());
   }
   if (D.pre) {
     GET(SSDT_SV_M, m);
     HIP_IF(wgrad(m, D.H, bf.dh1, D.F, D.T, gr->w_1, D.bias ? gr->b_1 : nullptr));
     HIP_IF(mm(D.T, D.H, D.F, bf.dh1, D.F, false, w->w_1, D.F, true, bf.t2, k::EPI_NONE, nullptr, nullptr));
+    HIP_IF(wgrad_flush());
     GET(cur_idx, cur); GET(SSDT_SV_RSTD2, rs2);
     const void *mu2 = nomean; if (D.ln) { GET(SSDT_SV_MEAN2, t); mu2 = t; }
     HIP_IF(nbwd(bf.t2, cur, mu2, rs2, w->ln2_g, dr2, bf.t1, gr->ln2_g, gr->ln2_b));
@@ -415,6 +456,7 @@ ssdt_status ssdt_layer_bwd(ssdt_ctx *ctx, const ssdt_layer_desc *desc, const ssd
     GET(SSDT_SV_X1, x1);
     HIP_IF(wgrad(x1, D.H, bf.dh1, D.F, D.T, gr->w_1, D.bias ? gr->b_1 : nullptr));
     HIP_IF(mm(D.T, D.H, D.F, bf.dh1, D.F, false, w->w_1, D.F, true, bf.t1, k::EPI_BIAS_RESID, dr2, nullptr));
+    HIP_IF(wgrad_flush());
   }
   void *dcur = bf.t1;  // gradient w.r.t. x2 (decoder) or x1
 
@@ -423,15 +465,18 @@ ssdt_status ssdt_layer_bwd(ssdt_ctx *ctx, const ssdt_layer_desc *desc, const ssd
     GET(SSDT_SV_OX, ox);
     HIP_IF(wgrad(ox, D.H, dcur, D.H, D.T, gr->w_ox, D.bias ? gr->b_ox : nullptr));
     HIP_IF(mm(D.T, D.H, D.H, dcur, D.H, false, w->w_ox, D.H, true, bf.t0, k::EPI_NONE, nullptr, nullptr));  // d ox
+    HIP_IF(wgrad_flush());
     GET(SSDT_SV_QX, qx); GET(SSDT_SV_KVX, kvx); GET(SSDT_SV_LSEX, lsex);
     HIP_IF(attn_b(qx, D.H, kvx, (const char *)kvx + D.H * e, 2 * D.H, D.S, D.Se, SSDT_MASK_NONE, ox, lsex, bf.t0,
                   bf.t2, D.H, bf.dkvx, (char *)bf.dkvx + D.H * e, 2 * D.H));  // d qx in t2
     GET(SSDT_SV_AX, ax);
     HIP_IF(wgrad(ax, D.H, bf.t2, D.H, D.T, gr->w_qx, D.bias ? gr->b_qx : nullptr));
     HIP_IF(mm(D.T, D.H, D.H, bf.t2, D.H, false, w->w_qx, D.H, true, bf.t0, k::EPI_NONE, nullptr, nullptr));  // d ax
+    HIP_IF(wgrad_flush());
     GET(SSDT_SV_ENC, enc);
     HIP_IF(wgrad(enc, D.H, bf.dkvx, 2 * D.H, D.Te, gr->w_kvx, D.bias ? gr->b_kvx : nullptr));
     HIP_IF(mm(D.Te, D.H, 2 * D.H, bf.dkvx, 2 * D.H, false, w->w_kvx, 2 * D.H, true, bf.denc, k::EPI_NONE, nullptr, nullptr));
+    HIP_IF(wgrad_flush());
     HIP_IF(k::add_inplace(d_enc_out, bf.denc, (size_t)D.Te * D.H, dt, st));
     GET(SSDT_SV_X1, x1); GET(SSDT_SV_RSTDX, rsx);
     const void *mux = nomean; if (D.ln) { GET(SSDT_SV_MEANX, t); mux = t; }
@@ -452,6 +497,7 @@ ssdt_status ssdt_layer_bwd(ssdt_ctx *ctx, const ssdt_layer_desc *desc, const ssd
   GET(SSDT_SV_O, o);
   HIP_IF(wgrad(o, D.H, dr1, D.H, D.T, gr->w_o, D.bias ? gr->b_o : nullptr));
   HIP_IF(mm(D.T, D.H, D.H, dr1, D.H, false, w->w_o, D.H, true, bf.t0, k::EPI_NONE, nullptr, nullptr));  // d o
+  HIP_IF(wgrad_flush());
   GET(SSDT_SV_QKV, qkv); GET(SSDT_SV_LSE, lse);
   HIP_IF(attn_b(qkv, 3 * D.H, (const char *)qkv + D.H * e, (const char *)qkv + 2 * D.H * e, 3 * D.H, D.S, D.S, desc->mask,
                 o, lse, bf.t0, bf.dqkv, 3 * D.H, (char *)bf.dqkv + D.H * e, (char *)bf.dqkv + 2 * D.H * e, 3 * D.H));
@@ -459,6 +505,7 @@ ssdt_status ssdt_layer_bwd(ssdt_ctx *ctx, const ssdt_layer_desc *desc, const ssd
     GET(SSDT_SV_A, a);
     HIP_IF(wgrad(a, D.H, bf.dqkv, 3 * D.H, D.T, gr->w_qkv, D.bias ? gr->b_qkv : nullptr));
     HIP_IF(mm(D.T, D.H, 3 * D.H, bf.dqkv, 3 * D.H, false, w->w_qkv, 3 * D.H, true, tA, k::EPI_NONE, nullptr, nullptr));  // d a
+    HIP_IF(wgrad_flush());
     GET(SSDT_SV_X, x); GET(SSDT_SV_RSTD1, rs1);
     const void *mu1 = nomean; if (D.ln) { GET(SSDT_SV_MEAN1, t); mu1 = t; }
     HIP_IF(nbwd(tA, x, mu1, rs1, w->ln1_g, dr1, dx, gr->ln1_g, gr->ln1_b));
@@ -466,7 +513,9 @@ ssdt_status ssdt_layer_bwd(ssdt_ctx *ctx, const ssdt_layer_desc *desc, const ssd
     GET(SSDT_SV_X, x);
     HIP_IF(wgrad(x, D.H, bf.dqkv, 3 * D.H, D.T, gr->w_qkv, D.bias ? gr->b_qkv : nullptr));
     HIP_IF(mm(D.T, D.H, 3 * D.H, bf.dqkv, 3 * D.H, false, w->w_qkv, 3 * D.H, true, dx, k::EPI_BIAS_RESID, dr1, nullptr));
+    HIP_IF(wgrad_flush());
   }
+  HIP_IF(wgrad_flush());
   return ctx->scope_end(scope, SSDT_BWD);
 #undef GET
 #undef HIP_IF
