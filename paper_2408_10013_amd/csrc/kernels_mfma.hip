@@ -115,17 +115,10 @@ __device__ __forceinline__ void unpack8f(const uint4 &v, float *f) {
 // 16 bytes per lane with 8 lanes covering 128 contiguous bytes of a row.  `st` is this wavefront's
 // private 64 x 68 float staging area; m_base / n_base are the sub-tile's origin.
 constexpr int kEpiLd = 68;
+// Second half of the staged epilogue: a 64x64 fp32 sub-tile sits row-major (leading dimension kEpiLd) in this
+// wavefront's staging area `st`; apply the epilogue and store it, 16 bytes per lane per access.
 template <int EPI>
-__device__ __forceinline__ void epilogue_staged(const NtP &p, const f32x16_t (&a0)[2], const f32x16_t (&a1)[2], float *st,
-                                                int m_base, int n_base, int lane) {
-  const int li = lane & 31, half = lane >> 5;
-#pragma unroll
-  for (int j = 0; j < 2; ++j)
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      *(float4 *)(st + li * kEpiLd + j * 32 + g * 8 + half * 4) = make_float4(a0[j][g * 4], a0[j][g * 4 + 1], a0[j][g * 4 + 2], a0[j][g * 4 + 3]);
-      *(float4 *)(st + (32 + li) * kEpiLd + j * 32 + g * 8 + half * 4) = make_float4(a1[j][g * 4], a1[j][g * 4 + 1], a1[j][g * 4 + 2], a1[j][g * 4 + 3]);
-    }
+__device__ __forceinline__ void epilogue_rows(const NtP &p, const float *st, int m_base, int n_base, int lane) {
   const int col0 = (lane & 7) * 8, n = n_base + col0;
   float b[8];
 #pragma unroll
@@ -157,6 +150,24 @@ __device__ __forceinline__ void epilogue_staged(const NtP &p, const f32x16_t (&a
       *(uint4 *)(p.C + o) = make_uint4(pack_bf2(v[0], v[1]), pack_bf2(v[2], v[3]), pack_bf2(v[4], v[5]), pack_bf2(v[6], v[7]));
     }
   }
+}
+
+// Epilogue of a 64x64 fp32 sub-tile held as 2x2 blocks of the 32x32 MFMA layout: the accumulators are written
+// to LDS in MFMA layout and read back row-major, so that every global access (bias, residual, activation
+// input, outputs) is 16 bytes per lane with 8 lanes covering 128 contiguous bytes of a row.  `st` is this
+// wavefront's private 64 x 68 float staging area; m_base / n_base are the sub-tile's origin.
+template <int EPI>
+__device__ __forceinline__ void epilogue_staged(const NtP &p, const f32x16_t (&a0)[2], const f32x16_t (&a1)[2], float *st,
+                                                int m_base, int n_base, int lane) {
+  const int li = lane & 31, half = lane >> 5;
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      *(float4 *)(st + li * kEpiLd + j * 32 + g * 8 + half * 4) = make_float4(a0[j][g * 4], a0[j][g * 4 + 1], a0[j][g * 4 + 2], a0[j][g * 4 + 3]);
+      *(float4 *)(st + (32 + li) * kEpiLd + j * 32 + g * 8 + half * 4) = make_float4(a1[j][g * 4], a1[j][g * 4 + 1], a1[j][g * 4 + 2], a1[j][g * 4 + 3]);
+    }
+  epilogue_rows<EPI>(p, st, m_base, n_base, lane);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -291,6 +302,188 @@ __global__ __launch_bounds__(512) void gemm_nt256_k(NtP p) {
 }
 
 // ------------------------------------------------------------------------------------------
+// 256x256 tile, v_mfma_f32_16x16x32_bf16, operand fragments streamed through the registers
+// ------------------------------------------------------------------------------------------
+// Same tile, same two 64 KiB LDS stages and the same swizzled rows as gemm_nt256_k, but
+//  * the 16x16x32 MFMA: on this (power-limited) part a loop of nothing but MFMAs on random operands
+//    sustains about 11 % more FLOP/s in this shape than in 32x32x16;
+//  * a stage is consumed as two 32-wide steps.  The A fragments of a step (8 blocks of 16 rows) live in
+//    one register set that is refilled block by block as soon as the MFMAs of a block have been issued,
+//    the Bt fragments in two sets that alternate per step: LDS reads are spread evenly over the MFMAs,
+//    every fragment is requested a whole step before it is used, and one `s_waitcnt lgkmcnt(MB-1+NB)`
+//    (a constant) in front of a block's MFMAs is all the waiting there is;
+//  * all reads of a stage have been issued by the end of its first step, so the one barrier per stage
+//    sits after the first block of its second step: behind it the next stage may be read and the stage
+//    after next may be loaded over the current one.  Those loads (direct global-to-LDS) go out one or two
+//    per block during the second step and have the whole first step of the next stage to land.
+// NB = 16-column blocks per wavefront: 4 -> 8 wavefronts of 128x64, 8 -> 4 wavefronts of 128x128.
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
+constexpr unsigned kStageBytes2 = kStage2 * 2;
+
+#define SSDT_WAITL(N, X) asm volatile("s_waitcnt lgkmcnt(" #N ")" : "+v"(X))
+
+template <int EPI, int NB>
+__global__ __launch_bounds__(NB == 4 ? 512 : 256) void gemm_nt256s_k(NtP p) {
+  constexpr int MB = 8, NT = NB == 4 ? 512 : 256, NWN = 256 / (NB * 16), LJ = 2048 / NT, RJ = NT / 8;
+  extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), wm = wave / NWN, wn = wave % NWN;
+  int tile_m, tile_n;
+  tile_of(p, blockIdx.x, &tile_m, &tile_n);
+  const int m0 = tile_m * kBM2, n0 = tile_n * kBN2;
+
+  // loader: thread t fills 16-byte positions j*NT + t of A and of Bt, j = 0..LJ-1: row j*RJ + t/8, slot t%8,
+  // which holds global chunk (t%8) ^ ((row >> 1) & 7); 8 consecutive lanes fetch one 128-byte line
+  const int lrow = tid >> 3, lchunk = (tid & 7) ^ ((lrow >> 1) & 7);
+  const uint16_t *ga = p.A + (long)(m0 + lrow) * p.lda + lchunk * 8;
+  const uint16_t *gb = p.Bt + (long)(n0 + lrow) * p.ldb + lchunk * 8;
+  const long aj = (long)RJ * p.lda, bj = (long)RJ * p.ldb;
+  uint16_t *s_wave = smem + wave * 512;  // a wavefront's 64 positions are contiguous: 1 KiB per load
+#define SSDT_LDA(st, j) __builtin_amdgcn_global_load_lds(ga + (j) * aj + (long)(st) * kBK2, (lds_void_t *)(s_wave + ((st) & 1) * kStage2 + (j) * NT * 8), 16, 0, 0)
+#define SSDT_LDB(st, j) __builtin_amdgcn_global_load_lds(gb + (j) * bj + (long)(st) * kBK2, (lds_void_t *)(s_wave + ((st) & 1) * kStage2 + kBM2 * kBK2 + (j) * NT * 8), 16, 0, 0)
+
+  f32x4_t acc[MB][NB];
+#pragma unroll
+  for (int i = 0; i < MB; ++i)
+#pragma unroll
+    for (int j = 0; j < NB; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+  const int nk = p.K / kBK2;
+#pragma unroll
+  for (int j = 0; j < LJ; ++j) { SSDT_LDA(0, j); SSDT_LDB(0, j); }
+  if (nk > 1) {
+#pragma unroll
+    for (int j = 0; j < LJ; ++j) { SSDT_LDA(1, j); SSDT_LDB(1, j); }
+  }
+
+  // fragment addresses: lane l reads row (l & 15) of a 16-row block, 16-byte chunk 4*kk + (l >> 4) of step kk
+  const int lr = lane & 15, lq = lane >> 4, lp = lr >> 1;
+  const unsigned lds0 = (unsigned)(uintptr_t)smem;
+  const unsigned arow = lds0 + (wm * 128 + lr) * 128, brow = lds0 + kBM2 * 128 + (wn * NB * 16 + lr) * 128;
+  // *_n: step 0 of the NEXT stage's buffer, *_c: step 1 of the CURRENT stage's buffer
+  unsigned aA_n = arow + ((lq ^ lp) * 16), aB_n = brow + ((lq ^ lp) * 16);
+  unsigned aA_c = arow + (((4 | lq) ^ lp) * 16), aB_c = brow + (((4 | lq) ^ lp) * 16);
+  v4i_t A0, A1, A2, A3, A4, A5, A6, A7, B[2][NB];
+
+#define SSDT_RDB(SET, addr)                                                                               \
+  {                                                                                                       \
+    SSDT_DSR(B[SET][0], addr, 0); SSDT_DSR(B[SET][1], addr, 2048); SSDT_DSR(B[SET][2], addr, 4096);       \
+    SSDT_DSR(B[SET][3], addr, 6144);                                                                      \
+    if constexpr (NB == 8) {                                                                              \
+      SSDT_DSR(B[SET][4], addr, 8192); SSDT_DSR(B[SET][5], addr, 10240); SSDT_DSR(B[SET][6], addr, 12288); \
+      SSDT_DSR(B[SET][7], addr, 14336);                                                                   \
+    }                                                                                                     \
+  }
+#define SSDT_MFROW(I, AI, SET)                                                                            \
+  {                                                                                                       \
+    _Pragma("unroll") for (int j = 0; j < NB; ++j)                                                        \
+      acc[I][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf(B[SET][j]), as_bf(AI), acc[I][j], 0, 0, 0); \
+  }
+// B set SET must be complete before its first use; tie it to the wait in front of block 0
+#define SSDT_TIEB(SET)                                                                                    \
+  {                                                                                                       \
+    asm volatile("" : "+v"(B[SET][0]), "+v"(B[SET][1]), "+v"(B[SET][2]), "+v"(B[SET][3]));                \
+    if constexpr (NB == 8) asm volatile("" : "+v"(B[SET][4]), "+v"(B[SET][5]), "+v"(B[SET][6]), "+v"(B[SET][7])); \
+  }
+// first step of a stage: block I on set 0, then refill AI with the block's fragment of the second step
+#define SSDT_EVEN(I, AI)                                                                                  \
+  {                                                                                                       \
+    if constexpr (NB == 4) SSDT_WAITL(11, AI); else SSDT_WAITL(15, AI);                                   \
+    if (I == 0) SSDT_TIEB(0);                                                                             \
+    __builtin_amdgcn_sched_barrier(0);                                                                    \
+    SSDT_MFROW(I, AI, 0);                                                                                 \
+    __builtin_amdgcn_sched_barrier(0);                                                                    \
+    SSDT_DSR(AI, aA_c, I * 2048);                                                                         \
+  }
+// second step, blocks 1..7: block I on set 1, refill AI from the next stage, LD = loads of the stage after next
+#define SSDT_ODD(I, AI, LD)                                                                               \
+  {                                                                                                       \
+    if (more2) { LD; }                                                                                    \
+    __builtin_amdgcn_sched_barrier(0);                                                                    \
+    SSDT_MFROW(I, AI, 1);                                                                                 \
+    __builtin_amdgcn_sched_barrier(0);                                                                    \
+    if (more) SSDT_DSR(AI, aA_n, I * 2048);                                                               \
+  }
+
+  if (nk > 1) {
+    if constexpr (NB == 4) __builtin_amdgcn_s_waitcnt(0xF70 | 8); else __builtin_amdgcn_s_waitcnt(0xF70 | 0 | (1 << 14));  // vmcnt(2*LJ): stage 0 landed
+  } else {
+    __builtin_amdgcn_s_waitcnt(0xF70);
+  }
+  __builtin_amdgcn_s_barrier();
+  SSDT_RDB(0, aB_n);
+  SSDT_DSR(A0, aA_n, 0); SSDT_DSR(A1, aA_n, 2048); SSDT_DSR(A2, aA_n, 4096); SSDT_DSR(A3, aA_n, 6144);
+  SSDT_DSR(A4, aA_n, 8192); SSDT_DSR(A5, aA_n, 10240); SSDT_DSR(A6, aA_n, 12288); SSDT_DSR(A7, aA_n, 14336);
+  aA_n += kStageBytes2; aB_n += kStageBytes2;
+  int delta = (int)kStageBytes2;
+
+  for (int st = 0; st < nk; ++st) {
+    const bool more = st + 1 < nk, more2 = st + 2 < nk;
+    // ---- first step of the stage
+    SSDT_RDB(1, aB_c);
+    SSDT_EVEN(0, A0); SSDT_EVEN(1, A1); SSDT_EVEN(2, A2); SSDT_EVEN(3, A3);
+    SSDT_EVEN(4, A4); SSDT_EVEN(5, A5); SSDT_EVEN(6, A6); SSDT_EVEN(7, A7);
+    // ---- second step: block 0, then the stage hand-over
+    SSDT_WAITL(7, A0);
+    SSDT_TIEB(1);
+    __builtin_amdgcn_sched_barrier(0);
+    SSDT_MFROW(0, A0, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    // every read of the current stage has returned to this wavefront
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(A1), "+v"(A2), "+v"(A3), "+v"(A4), "+v"(A5), "+v"(A6), "+v"(A7));
+    if (more) {
+      __builtin_amdgcn_s_waitcnt(0xF70);  // vmcnt(0): this wavefront's part of the next stage has landed
+      __builtin_amdgcn_s_barrier();       // so has everyone's, and nobody reads the current stage any more
+      SSDT_RDB(0, aB_n);
+      SSDT_DSR(A0, aA_n, 0);
+    }
+    if constexpr (NB == 4) {
+      SSDT_ODD(1, A1, { SSDT_LDA(st + 2, 0); SSDT_LDB(st + 2, 0); });
+      SSDT_ODD(2, A2, SSDT_LDA(st + 2, 1));
+      SSDT_ODD(3, A3, SSDT_LDB(st + 2, 1));
+      SSDT_ODD(4, A4, SSDT_LDA(st + 2, 2));
+      SSDT_ODD(5, A5, SSDT_LDB(st + 2, 2));
+      SSDT_ODD(6, A6, SSDT_LDA(st + 2, 3));
+      SSDT_ODD(7, A7, SSDT_LDB(st + 2, 3));
+    } else {
+      SSDT_ODD(1, A1, { SSDT_LDA(st + 2, 0); SSDT_LDB(st + 2, 0); SSDT_LDA(st + 2, 1); });
+      SSDT_ODD(2, A2, { SSDT_LDB(st + 2, 1); SSDT_LDA(st + 2, 2); SSDT_LDB(st + 2, 2); });
+      SSDT_ODD(3, A3, { SSDT_LDA(st + 2, 3); SSDT_LDB(st + 2, 3); });
+      SSDT_ODD(4, A4, { SSDT_LDA(st + 2, 4); SSDT_LDB(st + 2, 4); });
+      SSDT_ODD(5, A5, { SSDT_LDA(st + 2, 5); SSDT_LDB(st + 2, 5); });
+      SSDT_ODD(6, A6, { SSDT_LDA(st + 2, 6); SSDT_LDB(st + 2, 6); });
+      SSDT_ODD(7, A7, { SSDT_LDA(st + 2, 7); SSDT_LDB(st + 2, 7); });
+    }
+    aA_c += delta; aB_c += delta; aA_n -= delta; aB_n -= delta;
+    delta = -delta;
+  }
+#undef SSDT_LDA
+#undef SSDT_LDB
+#undef SSDT_RDB
+#undef SSDT_MFROW
+#undef SSDT_TIEB
+#undef SSDT_EVEN
+#undef SSDT_ODD
+  // epilogue through LDS (free now), 64x64 sub-tiles of the wavefront's tile: lane l of block (i, j) holds row
+  // i*16 + (l & 15), columns j*16 + (l >> 4)*4 + 0..3
+  __builtin_amdgcn_s_barrier();  // every wavefront has finished reading the last stage
+  float *stg = (float *)smem + wave * (64 * kEpiLd);
+#pragma unroll
+  for (int I = 0; I < MB / 4; ++I)
+#pragma unroll
+    for (int J = 0; J < NB / 4; ++J) {
+#pragma unroll
+      for (int il = 0; il < 4; ++il)
+#pragma unroll
+        for (int jl = 0; jl < 4; ++jl) {
+          const f32x4_t a = acc[I * 4 + il][J * 4 + jl];
+          *(float4 *)(stg + (il * 16 + lr) * kEpiLd + jl * 16 + lq * 4) = make_float4(a[0], a[1], a[2], a[3]);
+        }
+      epilogue_rows<EPI>(p, stg, m0 + wm * 128 + I * 64, n0 + wn * (NB * 16) + J * 64, lane);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
 // 128x128 tile, 4 wavefronts, register-staged double-buffered LDS (rows padded by 16 bytes)
 // ------------------------------------------------------------------------------------------
 constexpr int kBK = 64;
@@ -384,6 +577,21 @@ static hipError_t launch256(const NtP &p, hipStream_t s) {
   return hipGetLastError();
 }
 
+template <int EPI, int NB>
+static hipError_t launch256s(const NtP &p, hipStream_t s) {
+  constexpr int waves = NB == 4 ? 8 : 4;
+  constexpr size_t stg = (size_t)waves * 64 * kEpiLd * 4, stages = (size_t)2 * kStage2 * 2, smem = stg > stages ? stg : stages;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void *)gemm_nt256s_k<EPI, NB>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  prof::Scope ps(prof::GEMM_MFMA_256, 2.0 * p.M * p.N * p.K, 0, s);
+  hipLaunchKernelGGL((gemm_nt256s_k<EPI, NB>), dim3(p.tiles_m * p.tiles_n), dim3(waves * 64), smem, s, p);
+  return hipGetLastError();
+}
+
 template <int EPI>
 static hipError_t launch128(const NtP &p, hipStream_t s) {
   constexpr size_t smem = (size_t)2 * (128 + 128) * kLDK * 2;
@@ -400,9 +608,15 @@ static hipError_t launch128(const NtP &p, hipStream_t s) {
 
 int g_force_tile = 0;   // test hook: 0 = choose, 128 or 256
 int g_force_waves = 0;  // test hook: > 0 pins the tile rows per group of the workgroup order
+int g_gemm_variant = 0; // test hook: 256x256 kernel; 0 = choose, 1 = two-stage 32x32x16, 2 / 3 = streamed 16x16x32 with 8 / 4 wavefronts
 
 static hipError_t launch_epi(bool big, int epi, const NtP &p, hipStream_t s) {
-#define SSDT_CASE(E) case E: return big ? launch256<E>(p, s) : launch128<E>(p, s);
+#define SSDT_CASE(E)                                                                      \
+  case E:                                                                                 \
+    if (!big) return launch128<E>(p, s);                                                  \
+    if (g_gemm_variant == 1) return launch256<E>(p, s);                                   \
+    if (g_gemm_variant == 3) return launch256s<E, 8>(p, s);                               \
+    return launch256s<E, 4>(p, s);
   switch (epi) {
     SSDT_CASE(EPI_NONE)
     SSDT_CASE(EPI_BIAS)
