@@ -47,7 +47,6 @@ hipError_t gemm(const Gemm &g, hipStream_t s);
 hipError_t gemm_generic(const Gemm &g, hipStream_t s);  // the FMA kernel, any shape (gemm() falls back to it)
 extern int g_force_waves;                               // 0 = choose; > 0 pins the tile rows per workgroup-order group
 extern int g_attn_kb;                                   // 0 = choose; 1 pins the register-staged key-side attention backward
-extern int g_gemm_variant;                             // 0 = choose; 1 = two-stage 32x32x16 kernel; 2 / 3 = streamed 16x16x32 kernel, 8 / 4 wavefronts
 extern int g_force_tile;                                // 0 = choose; 128 / 256 pin the matrix-core tile
 // scratch bytes gemm() can make use of for this problem (0 for fp32)
 size_t gemm_scratch_bytes(int M, int N, int K, bool transA, bool transB, int dtype);

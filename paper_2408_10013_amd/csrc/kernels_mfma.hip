@@ -1,31 +1,28 @@
-// bf16 GEMM on the CDNA4 matrix cores (v_mfma_f32_32x32x16_bf16), fp32 accumulation.
+// bf16 GEMM on the CDNA4 matrix cores, fp32 accumulation.
 //
 // Both kernels compute C[M,N] = A[M,K] . Bt[N,K]^T with the two operands contiguous along K
 // ("NT"), the form the MFMA operand registers want (8 consecutive K per lane).  Other
 // transpositions are brought to this form by a transpose into caller scratch.
 //
 // gemm_nt256_k -- the workhorse, one workgroup of 8 wavefronts per 256x256 tile of C, each
-//   wavefront owning 128x64 as 4x2 MFMA blocks (128 accumulator registers, two wavefronts per
-//   SIMD so that one's LDS reads hide behind the other's MFMAs).  K is walked in steps of 64
-//   through two 64 KiB LDS stages filled by direct global-to-LDS loads (no staging registers,
-//   no LDS store instructions): a row of a stage is one whole 128-byte cache line, so the
-//   L2-to-L1 path moves no byte twice (with 32-wide steps every line was fetched twice and that
-//   path, about 50 B/clk per compute unit, became the bound).  The 16-byte chunk c of row r is
-//   kept at slot c ^ ((r >> 1) & 7), which makes the 128-bit operand reads of 16 consecutive
-//   rows fall on distinct banks without padding (the loader applies the permutation on the
-//   global side, since a direct load writes LDS linearly by lane).  Waiting is explicit: one
-//   `s_waitcnt vmcnt(0)` and one `s_barrier` per step, then the next step's loads are issued
-//   and run under this step's 32 MFMAs per wavefront.  LDS operand reads are issued through
-//   inline assembly, one 16-wide K sub-step ahead of the MFMAs that consume them, so that the
-//   compiler does not serialise them against the in-flight loads.
-// gemm_nt128_k -- 128x128 tiles, 4 wavefronts, register-staged double-buffered LDS; for
-//   problems too small to fill 256 compute units with 256x256 tiles.
+//   wavefront owning 128x64 as 8x4 blocks of v_mfma_f32_16x16x32_bf16 (128 accumulator
+//   registers, two wavefronts per SIMD).  That MFMA shape because the part is power-limited: a
+//   loop of nothing but MFMAs on random operands sustains about 11 % more FLOP/s (at a higher
+//   clock) in it than in 32x32x16.  K is walked in stages of 64 through two 64 KiB LDS buffers
+//   filled by direct global-to-LDS loads (no staging registers, no LDS store instructions): a
+//   row of a stage is one whole 128-byte cache line, so the L2-to-L1 path moves no byte twice.
+//   The 16-byte chunk c of row r is kept at slot c ^ ((r >> 1) & 7), which makes the 128-bit
+//   operand reads of 16 consecutive rows fall on distinct banks without padding (the loader
+//   applies the permutation on the global side, since a direct load writes LDS linearly by
+//   lane).  Loads, LDS reads and all waiting are written out (inline assembly, explicit
+//   `s_waitcnt`): see the kernel for the schedule.
+// gemm_nt128_k -- 128x128 tiles, 4 wavefronts, v_mfma_f32_32x32x16_bf16, register-staged
+//   double-buffered LDS; for problems too small to fill 256 compute units with 256x256 tiles.
 //
 // The MFMA is issued with the Bt fragment as its first operand, which leaves every lane with 4
-// consecutive columns of one row of C: epilogue traffic (bias, residual, activation input,
-// output) is 8 bytes per access.  Workgroup ids are remapped so that the ids one XCD receives
-// (id mod 8) cover a compact block of tiles, and tiles are visited in groups of rows, for L2
-// reuse.
+// consecutive columns of one row of C.  Workgroup ids are remapped so that the ids one XCD
+// receives (id mod 8) cover a compact block of tiles, and tiles are visited in groups of rows,
+// for L2 reuse.
 #include "dev.h"
 #include "kernels.h"
 #include "prof.h"
@@ -152,27 +149,6 @@ __device__ __forceinline__ void epilogue_rows(const NtP &p, const float *st, int
   }
 }
 
-// Epilogue of a 64x64 fp32 sub-tile held as 2x2 blocks of the 32x32 MFMA layout: the accumulators are written
-// to LDS in MFMA layout and read back row-major, so that every global access (bias, residual, activation
-// input, outputs) is 16 bytes per lane with 8 lanes covering 128 contiguous bytes of a row.  `st` is this
-// wavefront's private 64 x 68 float staging area; m_base / n_base are the sub-tile's origin.
-template <int EPI>
-__device__ __forceinline__ void epilogue_staged(const NtP &p, const f32x16_t (&a0)[2], const f32x16_t (&a1)[2], float *st,
-                                                int m_base, int n_base, int lane) {
-  const int li = lane & 31, half = lane >> 5;
-#pragma unroll
-  for (int j = 0; j < 2; ++j)
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      *(float4 *)(st + li * kEpiLd + j * 32 + g * 8 + half * 4) = make_float4(a0[j][g * 4], a0[j][g * 4 + 1], a0[j][g * 4 + 2], a0[j][g * 4 + 3]);
-      *(float4 *)(st + (32 + li) * kEpiLd + j * 32 + g * 8 + half * 4) = make_float4(a1[j][g * 4], a1[j][g * 4 + 1], a1[j][g * 4 + 2], a1[j][g * 4 + 3]);
-    }
-  epilogue_rows<EPI>(p, st, m_base, n_base, lane);
-}
-
-// ------------------------------------------------------------------------------------------
-// 256x256 tile, 8 wavefronts, two 64-wide LDS stages of direct global-to-LDS loads
-// ------------------------------------------------------------------------------------------
 constexpr int kBM2 = 256, kBN2 = 256, kBK2 = 64;
 constexpr int kStage2 = (kBM2 + kBN2) * kBK2;  // elements per stage: A rows then Bt rows, 128 bytes each
 
@@ -182,149 +158,34 @@ __device__ __forceinline__ bf16x8_t as_bf(v4i_t v) {
   return u.b;
 }
 #define SSDT_DSR(dst, addr, off) asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(off))
-// operands of one 16-wide K sub-step of a 128x64 wavefront tile: 4 A fragments, 2 Bt fragments
-#define SSDT_READ6(A0, A1, A2, A3, B0, B1, aaddr, baddr)                                                  \
-  {                                                                                                       \
-    SSDT_DSR(A0, aaddr, 0); SSDT_DSR(B0, baddr, 0); SSDT_DSR(A1, aaddr, 4096);                            \
-    SSDT_DSR(B1, baddr, 4096); SSDT_DSR(A2, aaddr, 8192); SSDT_DSR(A3, aaddr, 12288);                     \
-  }
-#define SSDT_WAIT6(N, A0, A1, A2, A3, B0, B1)                                                             \
-  asm volatile("s_waitcnt lgkmcnt(" #N ")" : "+v"(A0), "+v"(A1), "+v"(A2), "+v"(A3), "+v"(B0), "+v"(B1))
-#define SSDT_MFMA8(A0, A1, A2, A3, B0, B1)                                                                \
-  {                                                                                                       \
-    acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(B0), as_bf(A0), acc[0][0], 0, 0, 0);        \
-    acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(B1), as_bf(A0), acc[0][1], 0, 0, 0);        \
-    acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(B0), as_bf(A1), acc[1][0], 0, 0, 0);        \
-    acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(B1), as_bf(A1), acc[1][1], 0, 0, 0);        \
-    acc[2][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(B0), as_bf(A2), acc[2][0], 0, 0, 0);        \
-    acc[2][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(B1), as_bf(A2), acc[2][1], 0, 0, 0);        \
-    acc[3][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(B0), as_bf(A3), acc[3][0], 0, 0, 0);        \
-    acc[3][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf(B1), as_bf(A3), acc[3][1], 0, 0, 0);        \
-  }
-
-template <int EPI>
-__global__ __launch_bounds__(512) void gemm_nt256_k(NtP p) {
-  extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave >> 2, wn = wave & 3;
-  int tile_m, tile_n;
-  tile_of(p, blockIdx.x, &tile_m, &tile_n);
-  const int m0 = tile_m * kBM2, n0 = tile_n * kBN2;
-
-  // loader: thread t fills LDS positions j*512 + t (16-byte units), j = 0..3, of A and of Bt:
-  // row j*64 + t/8, slot t%8, which holds global chunk (t%8) ^ ((row >> 1) & 7) of that row;
-  // 8 consecutive lanes fetch one whole 128-byte line
-  const int lrow = tid >> 3, lchunk = (tid & 7) ^ ((lrow >> 1) & 7);
-  const uint16_t *ga = p.A + (long)(m0 + lrow) * p.lda + lchunk * 8;
-  const uint16_t *gb = p.Bt + (long)(n0 + lrow) * p.ldb + lchunk * 8;
-  const long a64 = 64 * p.lda, b64 = 64 * p.ldb;
-  uint16_t *s_wave = smem + wave * 64 * 8;  // a wavefront's 64 positions are contiguous: 1 KiB per load
-// two of the eight loads of a stage: the 64-row slices j of A and of Bt
-#define SSDT_ISSUE2(kt, j)                                                                                \
-  {                                                                                                       \
-    uint16_t *sb_ = s_wave + ((kt) & 1) * kStage2 + (j) * 64 * kBK2;                                      \
-    const long ko_ = (long)(kt) * kBK2;                                                                   \
-    __builtin_amdgcn_global_load_lds(ga + (j) * a64 + ko_, (lds_void_t *)(sb_), 16, 0, 0);                \
-    __builtin_amdgcn_global_load_lds(gb + (j) * b64 + ko_, (lds_void_t *)(sb_ + kBM2 * kBK2), 16, 0, 0);  \
-  }
-#define SSDT_ISSUE(kt) { SSDT_ISSUE2(kt, 0); SSDT_ISSUE2(kt, 1); SSDT_ISSUE2(kt, 2); SSDT_ISSUE2(kt, 3); }
-
-  f32x16_t acc[4][2];
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-  const int nk = p.K / kBK2;
-  SSDT_ISSUE(0);
-
-  const int li = lane & 31, half = lane >> 5;
-  const unsigned sw = (li >> 1) & 7;
-  const unsigned lds0 = (unsigned)(uintptr_t)smem;
-  // LDS byte addresses (stage 0) of this lane's first A / Bt fragment rows for the four sub-steps
-  const unsigned arow = lds0 + (wm * 128 + li) * 128, brow = lds0 + (kBM2 + wn * 64 + li) * 128;
-  const unsigned oa0 = arow + ((0 + half) ^ sw) * 16, oa1 = arow + ((2 + half) ^ sw) * 16;
-  const unsigned oa2 = arow + ((4 + half) ^ sw) * 16, oa3 = arow + ((6 + half) ^ sw) * 16;
-  const unsigned ob0 = brow + ((0 + half) ^ sw) * 16, ob1 = brow + ((2 + half) ^ sw) * 16;
-  const unsigned ob2 = brow + ((4 + half) ^ sw) * 16, ob3 = brow + ((6 + half) ^ sw) * 16;
-  v4i_t pa0, pa1, pa2, pa3, pb0, pb1, qa0, qa1, qa2, qa3, qb0, qb1;
-
-  // Software pipeline over the 64-wide stages.  A stage's four 16-wide sub-steps alternate between the
-  // register sets P and Q.  The wait for the next stage (its loads have landed, everyone is done reading
-  // the current one) sits BEFORE the last sub-step's MFMAs, once this wavefront holds all operands of the
-  // current stage: the first fragments of the next stage are then read under those MFMAs instead of under
-  // an idle matrix pipe.  The loads of the stage after next go out in small groups (1, 2, 1 pairs) at the
-  // barrier and in the first two sub-steps: a burst of all eight holds back the MFMAs queued behind it,
-  // a later issue leaves them too little time before the wait.
-  __builtin_amdgcn_s_waitcnt(0xF70);
-  __builtin_amdgcn_s_barrier();
-  if (nk > 1) SSDT_ISSUE2(1, 0);
-  SSDT_READ6(pa0, pa1, pa2, pa3, pb0, pb1, oa0, ob0);
-  for (int kt = 0; kt < nk; ++kt) {
-    const unsigned so = (kt & 1) * kStage2 * 2, so1 = ((kt + 1) & 1) * kStage2 * 2;
-    const bool more = kt + 1 < nk, more2 = kt + 2 < nk;
-    SSDT_READ6(qa0, qa1, qa2, qa3, qb0, qb1, oa1 + so, ob1 + so);
-    SSDT_WAIT6(6, pa0, pa1, pa2, pa3, pb0, pb1);
-    if (more) { SSDT_ISSUE2(kt + 1, 1); SSDT_ISSUE2(kt + 1, 2); }
-    __builtin_amdgcn_sched_barrier(0);
-    SSDT_MFMA8(pa0, pa1, pa2, pa3, pb0, pb1);
-    __builtin_amdgcn_sched_barrier(0);
-    SSDT_READ6(pa0, pa1, pa2, pa3, pb0, pb1, oa2 + so, ob2 + so);
-    SSDT_WAIT6(6, qa0, qa1, qa2, qa3, qb0, qb1);
-    if (more) SSDT_ISSUE2(kt + 1, 3);
-    __builtin_amdgcn_sched_barrier(0);
-    SSDT_MFMA8(qa0, qa1, qa2, qa3, qb0, qb1);
-    __builtin_amdgcn_sched_barrier(0);
-    SSDT_READ6(qa0, qa1, qa2, qa3, qb0, qb1, oa3 + so, ob3 + so);
-    SSDT_WAIT6(6, pa0, pa1, pa2, pa3, pb0, pb1);
-    __builtin_amdgcn_sched_barrier(0);
-    SSDT_MFMA8(pa0, pa1, pa2, pa3, pb0, pb1);
-    __builtin_amdgcn_sched_barrier(0);
-    SSDT_WAIT6(0, qa0, qa1, qa2, qa3, qb0, qb1);  // this wavefront now holds everything it needs of stage kt
-    if (more) {
-      __builtin_amdgcn_s_waitcnt(0xF70);  // vmcnt(0): its part of stage kt+1 has landed
-      __builtin_amdgcn_s_barrier();       // so has everyone's; and everyone is done reading stage kt
-      if (more2) SSDT_ISSUE2(kt + 2, 0);
-      SSDT_READ6(pa0, pa1, pa2, pa3, pb0, pb1, oa0 + so1, ob0 + so1);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    SSDT_MFMA8(qa0, qa1, qa2, qa3, qb0, qb1);
-    __builtin_amdgcn_sched_barrier(0);
-  }
-#undef SSDT_ISSUE2
-#undef SSDT_ISSUE
-  // epilogue through LDS (free now), two 64-row halves of the wavefront's 128x64 tile
-  __builtin_amdgcn_s_barrier();  // every wavefront has finished reading the last stage
-  float *stg = (float *)smem + wave * (64 * kEpiLd);
-  epilogue_staged<EPI>(p, acc[0], acc[1], stg, m0 + wm * 128, n0 + wn * 64, lane);
-  epilogue_staged<EPI>(p, acc[2], acc[3], stg, m0 + wm * 128 + 64, n0 + wn * 64, lane);
-}
 
 // ------------------------------------------------------------------------------------------
-// 256x256 tile, v_mfma_f32_16x16x32_bf16, operand fragments streamed through the registers
+// 256x256 tile, 8 wavefronts, v_mfma_f32_16x16x32_bf16, two 64-wide LDS stages of direct
+// global-to-LDS loads, operand fragments streamed through the registers
 // ------------------------------------------------------------------------------------------
-// Same tile, same two 64 KiB LDS stages and the same swizzled rows as gemm_nt256_k, but
-//  * the 16x16x32 MFMA: on this (power-limited) part a loop of nothing but MFMAs on random operands
-//    sustains about 11 % more FLOP/s in this shape than in 32x32x16;
-//  * a stage is consumed as two 32-wide steps.  The A fragments of a step (8 blocks of 16 rows) live in
-//    one register set that is refilled block by block as soon as the MFMAs of a block have been issued,
-//    the Bt fragments in two sets that alternate per step: LDS reads are spread evenly over the MFMAs,
-//    every fragment is requested a whole step before it is used, and one `s_waitcnt lgkmcnt(MB-1+NB)`
-//    (a constant) in front of a block's MFMAs is all the waiting there is;
-//  * all reads of a stage have been issued by the end of its first step, so the one barrier per stage
-//    sits after the first block of its second step: behind it the next stage may be read and the stage
-//    after next may be loaded over the current one.  Those loads (direct global-to-LDS) go out one or two
-//    per block during the second step and have the whole first step of the next stage to land.
-// NB = 16-column blocks per wavefront: 4 -> 8 wavefronts of 128x64, 8 -> 4 wavefronts of 128x128.
+// A stage (64 of K for all 512 rows, 64 KiB) is consumed as two 32-wide steps; a wavefront's 128x64 part of
+// the tile is 8 blocks of 16 rows of A against 4 blocks of 16 rows of Bt.
+//  * The A fragments of a step live in ONE register set that is refilled block by block as soon as the MFMAs
+//    of a block have been issued; the Bt fragments live in two sets that alternate per step.  LDS reads are
+//    thereby spread evenly over the MFMAs, every fragment is requested a whole step before it is used, and
+//    one `s_waitcnt lgkmcnt(11)` in front of a block's MFMAs is all the waiting there is: when block i of a
+//    step is about to start, the reads issued after the fragment it needs are always the 7 - i remaining
+//    refills of the previous step, the 4 Bt reads at the head of this step and the i refills of this step.
+//  * All reads of a stage have been issued by the end of its first step.  The single barrier per stage
+//    therefore sits after the first block of the second step (behind an `lgkmcnt(0)`: nobody reads the
+//    stage any more); behind it the next stage, whose loads were waited for just before, may be read, and
+//    the stage after next is loaded over the current one, one load behind the first MFMA of each remaining
+//    block.  Those loads have the whole first step of the next stage to land.
+//  * Loop control is peeled (steady state, second-to-last, last stage), the loads take their base from
+//    scalar registers: the steady-state loop contains no vector ALU instruction except four address adds.
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
 constexpr unsigned kStageBytes2 = kStage2 * 2;
 
-#define SSDT_WAITL(N, X) asm volatile("s_waitcnt lgkmcnt(" #N ")" : "+v"(X))
+#define SSDT_WAITL(N, X) asm volatile("s_waitcnt lgkmcnt(" #N ")\n\ts_nop 0" : "+v"(X))
 
-template <int EPI, int NB>
-__global__ __launch_bounds__(NB == 4 ? 512 : 256) void gemm_nt256s_k(NtP p) {
-  constexpr int MB = 8, NT = NB == 4 ? 512 : 256, NWN = 256 / (NB * 16), LJ = 2048 / NT, RJ = NT / 8;
+template <int EPI>
+__global__ __launch_bounds__(512) void gemm_nt256_k(NtP p) {
+  constexpr int MB = 8, NB = 4, NT = 512, NWN = 4, LJ = 2048 / NT, RJ = NT / 8;
   extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), wm = wave / NWN, wn = wave % NWN;
@@ -333,14 +194,27 @@ __global__ __launch_bounds__(NB == 4 ? 512 : 256) void gemm_nt256s_k(NtP p) {
   const int m0 = tile_m * kBM2, n0 = tile_n * kBN2;
 
   // loader: thread t fills 16-byte positions j*NT + t of A and of Bt, j = 0..LJ-1: row j*RJ + t/8, slot t%8,
-  // which holds global chunk (t%8) ^ ((row >> 1) & 7); 8 consecutive lanes fetch one 128-byte line
+  // which holds global chunk (t%8) ^ ((row >> 1) & 7); 8 consecutive lanes fetch one 128-byte line.  A load is
+  // `global_load_lds_dwordx4 voff, s[base]`: the base (tile and stage) sits in scalar registers and advances by
+  // scalar adds, the per-lane part is a 32-bit byte offset that never changes; M0 (the LDS destination of the
+  // wavefront's 1 KiB) is set in the same statement.  No instruction offset on the load: it would be added
+  // to the LDS address as well as to the global one.
   const int lrow = tid >> 3, lchunk = (tid & 7) ^ ((lrow >> 1) & 7);
-  const uint16_t *ga = p.A + (long)(m0 + lrow) * p.lda + lchunk * 8;
-  const uint16_t *gb = p.Bt + (long)(n0 + lrow) * p.ldb + lchunk * 8;
-  const long aj = (long)RJ * p.lda, bj = (long)RJ * p.ldb;
-  uint16_t *s_wave = smem + wave * 512;  // a wavefront's 64 positions are contiguous: 1 KiB per load
-#define SSDT_LDA(st, j) __builtin_amdgcn_global_load_lds(ga + (j) * aj + (long)(st) * kBK2, (lds_void_t *)(s_wave + ((st) & 1) * kStage2 + (j) * NT * 8), 16, 0, 0)
-#define SSDT_LDB(st, j) __builtin_amdgcn_global_load_lds(gb + (j) * bj + (long)(st) * kBK2, (lds_void_t *)(s_wave + ((st) & 1) * kStage2 + kBM2 * kBK2 + (j) * NT * 8), 16, 0, 0)
+  unsigned voa[LJ], vob[LJ];
+#pragma unroll
+  for (int j = 0; j < LJ; ++j) {
+    voa[j] = (unsigned)((lrow + j * RJ) * (int)p.lda + lchunk * 8) * 2u;
+    vob[j] = (unsigned)((lrow + j * RJ) * (int)p.ldb + lchunk * 8) * 2u;
+  }
+  const char *pa = (const char *)(p.A + (long)m0 * p.lda), *pb = (const char *)(p.Bt + (long)n0 * p.ldb);  // stage 0 of the tile
+  const unsigned lds0 = (unsigned)(uintptr_t)smem;
+  unsigned sb_c = lds0 + wave * 1024;  // LDS byte address of this wavefront's 1 KiB in the current stage's buffer
+// a load of the stage PTR points at into the LDS buffer whose wavefront base is SB
+#define SSDT_LD(SB, PTR, VOFF, LDSOFF)                                                                     \
+  asm volatile("s_add_u32 m0, %0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"                         \
+               :: "s"(SB), "v"(VOFF), "s"(PTR), "n"(LDSOFF) : "memory", "scc")
+#define SSDT_LDA(SB, PA, j) SSDT_LD(SB, PA, voa[j], (j) * NT * 16)
+#define SSDT_LDB(SB, PB, j) SSDT_LD(SB, PB, vob[j], kBM2 * kBK2 * 2 + (j) * NT * 16)
 
   f32x4_t acc[MB][NB];
 #pragma unroll
@@ -349,16 +223,18 @@ __global__ __launch_bounds__(NB == 4 ? 512 : 256) void gemm_nt256s_k(NtP p) {
     for (int j = 0; j < NB; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
   const int nk = p.K / kBK2;
-#pragma unroll
-  for (int j = 0; j < LJ; ++j) { SSDT_LDA(0, j); SSDT_LDB(0, j); }
+  SSDT_LDA(sb_c, pa, 0); SSDT_LDB(sb_c, pb, 0); SSDT_LDA(sb_c, pa, 1); SSDT_LDB(sb_c, pb, 1);
+  SSDT_LDA(sb_c, pa, 2); SSDT_LDB(sb_c, pb, 2); SSDT_LDA(sb_c, pa, 3); SSDT_LDB(sb_c, pb, 3);
   if (nk > 1) {
-#pragma unroll
-    for (int j = 0; j < LJ; ++j) { SSDT_LDA(1, j); SSDT_LDB(1, j); }
+    const unsigned sb1 = sb_c + kStageBytes2;
+    const char *pa1 = pa + kBK2 * 2, *pb1 = pb + kBK2 * 2;
+    SSDT_LDA(sb1, pa1, 0); SSDT_LDB(sb1, pb1, 0); SSDT_LDA(sb1, pa1, 1); SSDT_LDB(sb1, pb1, 1);
+    SSDT_LDA(sb1, pa1, 2); SSDT_LDB(sb1, pb1, 2); SSDT_LDA(sb1, pa1, 3); SSDT_LDB(sb1, pb1, 3);
   }
+  pa += 2 * kBK2 * 2; pb += 2 * kBK2 * 2;  // from here on: the stage after next
 
   // fragment addresses: lane l reads row (l & 15) of a 16-row block, 16-byte chunk 4*kk + (l >> 4) of step kk
   const int lr = lane & 15, lq = lane >> 4, lp = lr >> 1;
-  const unsigned lds0 = (unsigned)(uintptr_t)smem;
   const unsigned arow = lds0 + (wm * 128 + lr) * 128, brow = lds0 + kBM2 * 128 + (wn * NB * 16 + lr) * 128;
   // *_n: step 0 of the NEXT stage's buffer, *_c: step 1 of the CURRENT stage's buffer
   unsigned aA_n = arow + ((lq ^ lp) * 16), aB_n = brow + ((lq ^ lp) * 16);
@@ -369,118 +245,101 @@ __global__ __launch_bounds__(NB == 4 ? 512 : 256) void gemm_nt256s_k(NtP p) {
   {                                                                                                       \
     SSDT_DSR(B[SET][0], addr, 0); SSDT_DSR(B[SET][1], addr, 2048); SSDT_DSR(B[SET][2], addr, 4096);       \
     SSDT_DSR(B[SET][3], addr, 6144);                                                                      \
-    if constexpr (NB == 8) {                                                                              \
-      SSDT_DSR(B[SET][4], addr, 8192); SSDT_DSR(B[SET][5], addr, 10240); SSDT_DSR(B[SET][6], addr, 12288); \
-      SSDT_DSR(B[SET][7], addr, 14336);                                                                   \
-    }                                                                                                     \
   }
-#define SSDT_MFROW(I, AI, SET)                                                                            \
+// MFMAs j = J0..J1-1 of block I (row block I of A against Bt set SET), fenced so that nothing moves across
+#define SSDT_MF(I, AI, SET, J0, J1)                                                                       \
   {                                                                                                       \
-    _Pragma("unroll") for (int j = 0; j < NB; ++j)                                                        \
+    __builtin_amdgcn_sched_barrier(0);                                                                    \
+    _Pragma("unroll") for (int j = J0; j < J1; ++j)                                                       \
       acc[I][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf(B[SET][j]), as_bf(AI), acc[I][j], 0, 0, 0); \
+    __builtin_amdgcn_sched_barrier(0);                                                                    \
   }
-// B set SET must be complete before its first use; tie it to the wait in front of block 0
-#define SSDT_TIEB(SET)                                                                                    \
-  {                                                                                                       \
-    asm volatile("" : "+v"(B[SET][0]), "+v"(B[SET][1]), "+v"(B[SET][2]), "+v"(B[SET][3]));                \
-    if constexpr (NB == 8) asm volatile("" : "+v"(B[SET][4]), "+v"(B[SET][5]), "+v"(B[SET][6]), "+v"(B[SET][7])); \
-  }
+// Bt set SET must be complete before its first use; tie it to the wait in front of block 0
+#define SSDT_TIEB(SET) asm volatile("" : "+v"(B[SET][0]), "+v"(B[SET][1]), "+v"(B[SET][2]), "+v"(B[SET][3]))
 // first step of a stage: block I on set 0, then refill AI with the block's fragment of the second step
 #define SSDT_EVEN(I, AI)                                                                                  \
   {                                                                                                       \
-    if constexpr (NB == 4) SSDT_WAITL(11, AI); else SSDT_WAITL(15, AI);                                   \
+    SSDT_WAITL(11, AI);                                                                                   \
     if (I == 0) SSDT_TIEB(0);                                                                             \
-    __builtin_amdgcn_sched_barrier(0);                                                                    \
-    SSDT_MFROW(I, AI, 0);                                                                                 \
-    __builtin_amdgcn_sched_barrier(0);                                                                    \
+    SSDT_MF(I, AI, 0, 0, NB);                                                                             \
     SSDT_DSR(AI, aA_c, I * 2048);                                                                         \
   }
-// second step, blocks 1..7: block I on set 1, refill AI from the next stage, LD = loads of the stage after next
-#define SSDT_ODD(I, AI, LD)                                                                               \
+// second step, blocks 1..7: block I on set 1 with the loads L0, L1 of the stage after next slotted in behind
+// its first MFMAs (a load is three scalar-side instructions, which fit behind one MFMA), then the refill of
+// AI from the next stage
+#define SSDT_ODD(MORE, MORE2, I, AI, L0, L1)                                                              \
   {                                                                                                       \
-    if (more2) { LD; }                                                                                    \
-    __builtin_amdgcn_sched_barrier(0);                                                                    \
-    SSDT_MFROW(I, AI, 1);                                                                                 \
-    __builtin_amdgcn_sched_barrier(0);                                                                    \
-    if (more) SSDT_DSR(AI, aA_n, I * 2048);                                                               \
+    SSDT_MF(I, AI, 1, 0, 1);                                                                              \
+    if (MORE2) { L0; }                                                                                    \
+    SSDT_MF(I, AI, 1, 1, 2);                                                                              \
+    if (MORE2) { L1; }                                                                                    \
+    SSDT_MF(I, AI, 1, 2, NB);                                                                             \
+    if (MORE) SSDT_DSR(AI, aA_n, I * 2048);                                                               \
+  }
+// One stage.  MORE / MORE2 (literals): a next stage / a stage after next exists.
+#define SSDT_STAGE(MORE, MORE2)                                                                           \
+  {                                                                                                       \
+    SSDT_RDB(1, aB_c);                                                                                    \
+    SSDT_EVEN(0, A0); SSDT_EVEN(1, A1); SSDT_EVEN(2, A2); SSDT_EVEN(3, A3);                               \
+    SSDT_EVEN(4, A4); SSDT_EVEN(5, A5); SSDT_EVEN(6, A6); SSDT_EVEN(7, A7);                               \
+    SSDT_WAITL(7, A0);                                                                                    \
+    SSDT_TIEB(1);                                                                                         \
+    SSDT_MF(0, A0, 1, 0, NB);                                                                             \
+    /* every read of the current stage has returned to this wavefront */                                  \
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_nop 0" : "+v"(A1), "+v"(A2), "+v"(A3), "+v"(A4), "+v"(A5), "+v"(A6), "+v"(A7)); \
+    if (MORE) {                                                                                           \
+      __builtin_amdgcn_s_waitcnt(0xF70); /* vmcnt(0): this wavefront's part of the next stage has landed */ \
+      __builtin_amdgcn_s_barrier();      /* so has everyone's, and nobody reads the current stage any more */ \
+      SSDT_RDB(0, aB_n);                                                                                  \
+      SSDT_DSR(A0, aA_n, 0);                                                                              \
+    }                                                                                                     \
+    SSDT_ODD(MORE, MORE2, 1, A1, SSDT_LDA(sb_c, pa, 0), SSDT_LDB(sb_c, pb, 0));                           \
+    SSDT_ODD(MORE, MORE2, 2, A2, SSDT_LDA(sb_c, pa, 1), );                                                \
+    SSDT_ODD(MORE, MORE2, 3, A3, SSDT_LDB(sb_c, pb, 1), );                                                \
+    SSDT_ODD(MORE, MORE2, 4, A4, SSDT_LDA(sb_c, pa, 2), );                                                \
+    SSDT_ODD(MORE, MORE2, 5, A5, SSDT_LDB(sb_c, pb, 2), );                                                \
+    SSDT_ODD(MORE, MORE2, 6, A6, SSDT_LDA(sb_c, pa, 3), );                                                \
+    SSDT_ODD(MORE, MORE2, 7, A7, SSDT_LDB(sb_c, pb, 3), );                                                \
+    aA_c += delta; aB_c += delta; aA_n -= delta; aB_n -= delta; sb_c += delta;                            \
+    delta = -delta;                                                                                       \
+    pa += kBK2 * 2; pb += kBK2 * 2;                                                                       \
   }
 
-  if (nk > 1) {
-    if constexpr (NB == 4) __builtin_amdgcn_s_waitcnt(0xF70 | 8); else __builtin_amdgcn_s_waitcnt(0xF70 | 0 | (1 << 14));  // vmcnt(2*LJ): stage 0 landed
-  } else {
-    __builtin_amdgcn_s_waitcnt(0xF70);
-  }
+  // vmcnt(2*LJ): stage 0 has landed (stage 1 may still be on its way)
+  if (nk > 1) __builtin_amdgcn_s_waitcnt(0xF70 | 8); else __builtin_amdgcn_s_waitcnt(0xF70);
   __builtin_amdgcn_s_barrier();
   SSDT_RDB(0, aB_n);
   SSDT_DSR(A0, aA_n, 0); SSDT_DSR(A1, aA_n, 2048); SSDT_DSR(A2, aA_n, 4096); SSDT_DSR(A3, aA_n, 6144);
   SSDT_DSR(A4, aA_n, 8192); SSDT_DSR(A5, aA_n, 10240); SSDT_DSR(A6, aA_n, 12288); SSDT_DSR(A7, aA_n, 14336);
   aA_n += kStageBytes2; aB_n += kStageBytes2;
-  int delta = (int)kStageBytes2;
-
-  for (int st = 0; st < nk; ++st) {
-    const bool more = st + 1 < nk, more2 = st + 2 < nk;
-    // ---- first step of the stage
-    SSDT_RDB(1, aB_c);
-    SSDT_EVEN(0, A0); SSDT_EVEN(1, A1); SSDT_EVEN(2, A2); SSDT_EVEN(3, A3);
-    SSDT_EVEN(4, A4); SSDT_EVEN(5, A5); SSDT_EVEN(6, A6); SSDT_EVEN(7, A7);
-    // ---- second step: block 0, then the stage hand-over
-    SSDT_WAITL(7, A0);
-    SSDT_TIEB(1);
-    __builtin_amdgcn_sched_barrier(0);
-    SSDT_MFROW(0, A0, 1);
-    __builtin_amdgcn_sched_barrier(0);
-    // every read of the current stage has returned to this wavefront
-    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(A1), "+v"(A2), "+v"(A3), "+v"(A4), "+v"(A5), "+v"(A6), "+v"(A7));
-    if (more) {
-      __builtin_amdgcn_s_waitcnt(0xF70);  // vmcnt(0): this wavefront's part of the next stage has landed
-      __builtin_amdgcn_s_barrier();       // so has everyone's, and nobody reads the current stage any more
-      SSDT_RDB(0, aB_n);
-      SSDT_DSR(A0, aA_n, 0);
-    }
-    if constexpr (NB == 4) {
-      SSDT_ODD(1, A1, { SSDT_LDA(st + 2, 0); SSDT_LDB(st + 2, 0); });
-      SSDT_ODD(2, A2, SSDT_LDA(st + 2, 1));
-      SSDT_ODD(3, A3, SSDT_LDB(st + 2, 1));
-      SSDT_ODD(4, A4, SSDT_LDA(st + 2, 2));
-      SSDT_ODD(5, A5, SSDT_LDB(st + 2, 2));
-      SSDT_ODD(6, A6, SSDT_LDA(st + 2, 3));
-      SSDT_ODD(7, A7, SSDT_LDB(st + 2, 3));
-    } else {
-      SSDT_ODD(1, A1, { SSDT_LDA(st + 2, 0); SSDT_LDB(st + 2, 0); SSDT_LDA(st + 2, 1); });
-      SSDT_ODD(2, A2, { SSDT_LDB(st + 2, 1); SSDT_LDA(st + 2, 2); SSDT_LDB(st + 2, 2); });
-      SSDT_ODD(3, A3, { SSDT_LDA(st + 2, 3); SSDT_LDB(st + 2, 3); });
-      SSDT_ODD(4, A4, { SSDT_LDA(st + 2, 4); SSDT_LDB(st + 2, 4); });
-      SSDT_ODD(5, A5, { SSDT_LDA(st + 2, 5); SSDT_LDB(st + 2, 5); });
-      SSDT_ODD(6, A6, { SSDT_LDA(st + 2, 6); SSDT_LDB(st + 2, 6); });
-      SSDT_ODD(7, A7, { SSDT_LDA(st + 2, 7); SSDT_LDB(st + 2, 7); });
-    }
-    aA_c += delta; aB_c += delta; aA_n -= delta; aB_n -= delta;
-    delta = -delta;
-  }
+  int delta = (int)kStageBytes2, st = 0;
+  for (; st + 2 < nk; ++st) SSDT_STAGE(true, true);
+  if (st + 1 < nk) SSDT_STAGE(true, false);
+  SSDT_STAGE(false, false);
+#undef SSDT_LD
 #undef SSDT_LDA
 #undef SSDT_LDB
 #undef SSDT_RDB
-#undef SSDT_MFROW
+#undef SSDT_MF
 #undef SSDT_TIEB
 #undef SSDT_EVEN
 #undef SSDT_ODD
-  // epilogue through LDS (free now), 64x64 sub-tiles of the wavefront's tile: lane l of block (i, j) holds row
-  // i*16 + (l & 15), columns j*16 + (l >> 4)*4 + 0..3
+#undef SSDT_STAGE
+  // epilogue through LDS (free now), two 64x64 sub-tiles of the wavefront's 128x64: lane l of block (i, j) holds
+  // row i*16 + (l & 15), columns j*16 + (l >> 4)*4 + 0..3
   __builtin_amdgcn_s_barrier();  // every wavefront has finished reading the last stage
   float *stg = (float *)smem + wave * (64 * kEpiLd);
 #pragma unroll
-  for (int I = 0; I < MB / 4; ++I)
+  for (int I = 0; I < MB / 4; ++I) {
 #pragma unroll
-    for (int J = 0; J < NB / 4; ++J) {
+    for (int il = 0; il < 4; ++il)
 #pragma unroll
-      for (int il = 0; il < 4; ++il)
-#pragma unroll
-        for (int jl = 0; jl < 4; ++jl) {
-          const f32x4_t a = acc[I * 4 + il][J * 4 + jl];
-          *(float4 *)(stg + (il * 16 + lr) * kEpiLd + jl * 16 + lq * 4) = make_float4(a[0], a[1], a[2], a[3]);
-        }
-      epilogue_rows<EPI>(p, stg, m0 + wm * 128 + I * 64, n0 + wn * (NB * 16) + J * 64, lane);
-    }
+      for (int jl = 0; jl < 4; ++jl) {
+        const f32x4_t a = acc[I * 4 + il][jl];
+        *(float4 *)(stg + (il * 16 + lr) * kEpiLd + jl * 16 + lq * 4) = make_float4(a[0], a[1], a[2], a[3]);
+      }
+    epilogue_rows<EPI>(p, stg, m0 + wm * 128 + I * 64, n0 + wn * 64, lane);
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -565,7 +424,7 @@ __global__ __launch_bounds__(256) void gemm_nt128_k(NtP p) {
 
 template <int EPI>
 static hipError_t launch256(const NtP &p, hipStream_t s) {
-  constexpr size_t smem = (size_t)8 * 64 * kEpiLd * 4 > (size_t)2 * kStage2 * 2 ? (size_t)8 * 64 * kEpiLd * 4 : (size_t)2 * kStage2 * 2;
+  constexpr size_t stg = (size_t)8 * 64 * kEpiLd * 4, stages = (size_t)2 * kStage2 * 2, smem = stg > stages ? stg : stages;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void *)gemm_nt256_k<EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -574,21 +433,6 @@ static hipError_t launch256(const NtP &p, hipStream_t s) {
   }
   prof::Scope ps(prof::GEMM_MFMA_256, 2.0 * p.M * p.N * p.K, 0, s);
   hipLaunchKernelGGL((gemm_nt256_k<EPI>), dim3(p.tiles_m * p.tiles_n), dim3(512), smem, s, p);
-  return hipGetLastError();
-}
-
-template <int EPI, int NB>
-static hipError_t launch256s(const NtP &p, hipStream_t s) {
-  constexpr int waves = NB == 4 ? 8 : 4;
-  constexpr size_t stg = (size_t)waves * 64 * kEpiLd * 4, stages = (size_t)2 * kStage2 * 2, smem = stg > stages ? stg : stages;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void *)gemm_nt256s_k<EPI, NB>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
-  prof::Scope ps(prof::GEMM_MFMA_256, 2.0 * p.M * p.N * p.K, 0, s);
-  hipLaunchKernelGGL((gemm_nt256s_k<EPI, NB>), dim3(p.tiles_m * p.tiles_n), dim3(waves * 64), smem, s, p);
   return hipGetLastError();
 }
 
@@ -608,15 +452,9 @@ static hipError_t launch128(const NtP &p, hipStream_t s) {
 
 int g_force_tile = 0;   // test hook: 0 = choose, 128 or 256
 int g_force_waves = 0;  // test hook: > 0 pins the tile rows per group of the workgroup order
-int g_gemm_variant = 0; // test hook: 256x256 kernel; 0 = choose, 1 = two-stage 32x32x16, 2 / 3 = streamed 16x16x32 with 8 / 4 wavefronts
 
 static hipError_t launch_epi(bool big, int epi, const NtP &p, hipStream_t s) {
-#define SSDT_CASE(E)                                                                      \
-  case E:                                                                                 \
-    if (!big) return launch128<E>(p, s);                                                  \
-    if (g_gemm_variant == 1) return launch256<E>(p, s);                                   \
-    if (g_gemm_variant == 3) return launch256s<E, 8>(p, s);                               \
-    return launch256s<E, 4>(p, s);
+#define SSDT_CASE(E) case E: return big ? launch256<E>(p, s) : launch128<E>(p, s);
   switch (epi) {
     SSDT_CASE(EPI_NONE)
     SSDT_CASE(EPI_BIAS)
