@@ -174,8 +174,9 @@ __device__ __forceinline__ bf16x8_t as_bf(v4i_t v) {
 //  * All reads of a stage have been issued by the end of its first step.  The single barrier per stage
 //    therefore sits after the first block of the second step (behind an `lgkmcnt(0)`: nobody reads the
 //    stage any more); behind it the next stage, whose loads were waited for just before, may be read, and
-//    the stage after next is loaded over the current one, one load behind the first MFMA of each remaining
-//    block.  Those loads have the whole first step of the next stage to land.
+//    the stage after next is loaded over the current one, two loads per block behind the first MFMAs of
+//    blocks 1..4 (measured against one load per block and against four per block: +0.6 % and +1.5 %).
+//    Those loads have the rest of the step and the whole first step of the next stage to land.
 //  * Loop control is peeled (steady state, second-to-last, last stage), the loads take their base from
 //    scalar registers: the steady-state loop contains no vector ALU instruction except four address adds.
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
@@ -294,12 +295,12 @@ __global__ __launch_bounds__(512) void gemm_nt256_k(NtP p) {
       SSDT_DSR(A0, aA_n, 0);                                                                              \
     }                                                                                                     \
     SSDT_ODD(MORE, MORE2, 1, A1, SSDT_LDA(sb_c, pa, 0), SSDT_LDB(sb_c, pb, 0));                           \
-    SSDT_ODD(MORE, MORE2, 2, A2, SSDT_LDA(sb_c, pa, 1), );                                                \
-    SSDT_ODD(MORE, MORE2, 3, A3, SSDT_LDB(sb_c, pb, 1), );                                                \
-    SSDT_ODD(MORE, MORE2, 4, A4, SSDT_LDA(sb_c, pa, 2), );                                                \
-    SSDT_ODD(MORE, MORE2, 5, A5, SSDT_LDB(sb_c, pb, 2), );                                                \
-    SSDT_ODD(MORE, MORE2, 6, A6, SSDT_LDA(sb_c, pa, 3), );                                                \
-    SSDT_ODD(MORE, MORE2, 7, A7, SSDT_LDB(sb_c, pb, 3), );                                                \
+    SSDT_ODD(MORE, MORE2, 2, A2, SSDT_LDA(sb_c, pa, 1), SSDT_LDB(sb_c, pb, 1));                           \
+    SSDT_ODD(MORE, MORE2, 3, A3, SSDT_LDA(sb_c, pa, 2), SSDT_LDB(sb_c, pb, 2));                           \
+    SSDT_ODD(MORE, MORE2, 4, A4, SSDT_LDA(sb_c, pa, 3), SSDT_LDB(sb_c, pb, 3));                           \
+    SSDT_ODD(MORE, MORE2, 5, A5, , );                                                                     \
+    SSDT_ODD(MORE, MORE2, 6, A6, , );                                                                     \
+    SSDT_ODD(MORE, MORE2, 7, A7, , );                                                                     \
     aA_c += delta; aB_c += delta; aA_n -= delta; aB_n -= delta; sb_c += delta;                            \
     delta = -delta;                                                                                       \
     pa += kBK2 * 2; pb += kBK2 * 2;                                                                       \
@@ -473,8 +474,8 @@ static inline bool al8(const void *p) { return ((uintptr_t)p & 7) == 0; }
 size_t gemm_scratch_bytes(int M, int N, int K, bool transA, bool transB, int dtype) {
   if (dtype != SSDT_BF16) return 0;
   size_t b = 0;
-  if (transA) b += up((size_t)M * K * 2, 256);
-  if (!transB) b += up((size_t)N * K * 2, 256);
+  if (transA) b += up((size_t)M * nt_copy_ld(K) * 2, 256);
+  if (!transB) b += up((size_t)N * nt_copy_ld(K) * 2, 256);
   return b;
 }
 
@@ -493,18 +494,19 @@ hipError_t gemm_mfma_bf16(const Gemm &g, hipStream_t s) {
   const uint16_t *A = (const uint16_t *)g.A, *Bt = (const uint16_t *)g.B;
   long lda = g.lda, ldb = g.ldb;
   char *sc = (char *)g.scratch;
+  const long ldk = nt_copy_ld(g.K);
   if (g.transA) {  // stored [K, M] -> [M, K]
-    hipError_t e = transpose(g.A, g.lda, sc, g.K, g.K, g.M, SSDT_BF16, s);
+    hipError_t e = transpose(g.A, g.lda, sc, ldk, g.K, g.M, SSDT_BF16, s);
     if (e != hipSuccess) return e;
     A = (const uint16_t *)sc;
-    lda = g.K;
-    sc += up((size_t)g.M * g.K * 2, 256);
+    lda = ldk;
+    sc += up((size_t)g.M * ldk * 2, 256);
   }
   if (!g.transB) {  // stored [K, N] -> [N, K]
-    hipError_t e = transpose(g.B, g.ldb, sc, g.K, g.K, g.N, SSDT_BF16, s);
+    hipError_t e = transpose(g.B, g.ldb, sc, ldk, g.K, g.N, SSDT_BF16, s);
     if (e != hipSuccess) return e;
     Bt = (const uint16_t *)sc;
-    ldb = g.K;
+    ldb = ldk;
   }
   if (!al16(A) || !al16(Bt) || lda % 8 || ldb % 8) return hipErrorNotSupported;
   NtP p{g.M, g.N, g.K, A, Bt, lda, ldb, g.ldc, g.ldr, (uint16_t *)g.C, (uint16_t *)g.C2, (const uint16_t *)g.bias,

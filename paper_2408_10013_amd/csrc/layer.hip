@@ -372,20 +372,21 @@ ssdt_status ssdt_layer_bwd(ssdt_ctx *ctx, const ssdt_layer_desc *desc, const ssd
   // enqueues the weight-gradient GEMM.  The side stream's next round starts only after an event recorded behind that
   // GEMM on the caller's stream (a later dY depends on it in stream order anyway), so one scratch area suffices.
   hipStream_t side = (hipStream_t)ctx->be->aux_stream();
-  struct Pending { bool on = false; int Kin, Nout, rows; void *dW; const uint16_t *At, *Bt; Ev *ready; } pend;
+  struct Pending { bool on = false; int Kin, Nout, rows; long ld; void *dW; const uint16_t *At, *Bt; Ev *ready; } pend;
   auto wgrad_flush = [&]() -> hipError_t {
     if (!pend.on) return hipSuccess;
     pend.on = false;
     ctx->be->wait(stream, pend.ready);
     drop(ctx->be.get(), pend.ready);
     k::Gemm g;
-    g.M = pend.Kin; g.N = pend.Nout; g.K = pend.rows; g.A = pend.At; g.lda = pend.rows; g.transA = false; g.B = pend.Bt;
-    g.ldb = pend.rows; g.transB = true; g.C = pend.dW; g.ldc = pend.Nout; g.epi = accum ? k::EPI_BIAS_RESID : k::EPI_NONE;
+    g.M = pend.Kin; g.N = pend.Nout; g.K = pend.rows; g.A = pend.At; g.lda = pend.ld; g.transA = false; g.B = pend.Bt;
+    g.ldb = pend.ld; g.transB = true; g.C = pend.dW; g.ldc = pend.Nout; g.epi = accum ? k::EPI_BIAS_RESID : k::EPI_NONE;
     g.resid = accum ? pend.dW : nullptr; g.ldr = pend.Nout; g.act = desc->act; g.dtype = dt;
     return k::gemm(g, st);
   };
   auto wgrad = [&](const void *in, int Kin, const void *dY, int Nout, int rows, void *dW, void *db) -> hipError_t {
-    const size_t a_bytes = ((size_t)Kin * rows * 2 + 255) / 256 * 256, b_bytes = (size_t)Nout * rows * 2;
+    const long ld = k::nt_copy_ld(rows);  // leading dimension of the two transposed copies
+    const size_t a_bytes = ((size_t)Kin * ld * 2 + 255) / 256 * 256, b_bytes = (size_t)Nout * ld * 2;
     const bool overlap = side && dt == SSDT_BF16 && Kin % 128 == 0 && Nout % 128 == 0 && rows % 64 == 0 &&
                          a_bytes + b_bytes <= bf.scratch_bytes;
     if (!overlap) {
@@ -401,11 +402,11 @@ ssdt_status ssdt_layer_bwd(ssdt_ctx *ctx, const ssdt_layer_desc *desc, const ssd
     ctx->be->wait(side, go);
     drop(ctx->be.get(), go);
     uint16_t *At = (uint16_t *)bf.scratch, *Bt = (uint16_t *)((char *)bf.scratch + a_bytes);
-    hipError_t e1 = k::transpose(in, Kin, At, rows, rows, Kin, SSDT_BF16, side);     // [rows, Kin] -> [Kin, rows]
-    if (e1 == hipSuccess) e1 = k::transpose(dY, Nout, Bt, rows, rows, Nout, SSDT_BF16, side);  // [rows, Nout] -> [Nout, rows]
+    hipError_t e1 = k::transpose(in, Kin, At, ld, rows, Kin, SSDT_BF16, side);     // [rows, Kin] -> [Kin, rows]
+    if (e1 == hipSuccess) e1 = k::transpose(dY, Nout, Bt, ld, rows, Nout, SSDT_BF16, side);  // [rows, Nout] -> [Nout, rows]
     if (e1 == hipSuccess && db) e1 = k::colsum(dY, Nout, db, bf.partial_side, rows, Nout, dt, accum, side);
     if (e1 != hipSuccess) return e1;
-    pend.on = true; pend.Kin = Kin; pend.Nout = Nout; pend.rows = rows; pend.dW = dW; pend.At = At; pend.Bt = Bt;
+    pend.on = true; pend.Kin = Kin; pend.Nout = Nout; pend.rows = rows; pend.ld = ld; pend.dW = dW; pend.At = At; pend.Bt = Bt;
     pend.ready = hold(ctx->be->record(side, false));
     return hipSuccess;
   };
