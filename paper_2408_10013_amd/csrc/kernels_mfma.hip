@@ -112,6 +112,20 @@ __device__ __forceinline__ void unpack8f(const uint4 &v, float *f) {
 // 16 bytes per lane with 8 lanes covering 128 contiguous bytes of a row.  `st` is this wavefront's
 // private 64 x 68 float staging area; m_base / n_base are the sub-tile's origin.
 constexpr int kEpiLd = 68;
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+// Streaming accesses of the epilogue: every output line is written once and read by a later kernel only after
+// far more than an L2's worth of other data, residual and activation inputs are read once.  Marked
+// non-temporal they do not displace the operand panels the other workgroups of the XCD are sharing
+// (measured: +3-4 % on a whole 32768 x 8192 x 8192 GEMM; the stores alone cost 7 % when left cacheable).
+__device__ __forceinline__ void store8_nt(uint16_t *dst, const float *v) {
+  const u32x4_t q = {pack_bf2(v[0], v[1]), pack_bf2(v[2], v[3]), pack_bf2(v[4], v[5]), pack_bf2(v[6], v[7])};
+  __builtin_nontemporal_store(q, (u32x4_t *)dst);
+}
+__device__ __forceinline__ void load8f_nt(const uint16_t *src, float *f) {
+  const u32x4_t q = __builtin_nontemporal_load((const u32x4_t *)src);
+  unpack8f(make_uint4(q.x, q.y, q.z, q.w), f);
+}
+
 // Second half of the staged epilogue: a 64x64 fp32 sub-tile sits row-major (leading dimension kEpiLd) in this
 // wavefront's staging area `st`; apply the epilogue and store it, 16 bytes per lane per access.
 template <int EPI>
@@ -128,23 +142,23 @@ __device__ __forceinline__ void epilogue_rows(const NtP &p, const float *st, int
     float v[8] = {lo.x + b[0], lo.y + b[1], lo.z + b[2], lo.w + b[3], hi.x + b[4], hi.y + b[5], hi.z + b[6], hi.w + b[7]};
     const long o = (long)m * p.ldc + n;
     if (EPI == EPI_BIAS_ACT) {
-      if (p.C) *(uint4 *)(p.C + o) = make_uint4(pack_bf2(v[0], v[1]), pack_bf2(v[2], v[3]), pack_bf2(v[4], v[5]), pack_bf2(v[6], v[7]));
+      if (p.C) store8_nt(p.C + o, v);
 #pragma unroll
       for (int t = 0; t < 8; ++t) v[t] = p.act == SSDT_ACT_GELU ? gelu_f(v[t]) : fmaxf(v[t], 0.f);
-      *(uint4 *)(p.C2 + o) = make_uint4(pack_bf2(v[0], v[1]), pack_bf2(v[2], v[3]), pack_bf2(v[4], v[5]), pack_bf2(v[6], v[7]));
+      store8_nt(p.C2 + o, v);
     } else {
       if (EPI == EPI_BIAS_RESID) {
         float r[8];
-        unpack8f(*(const uint4 *)(p.resid + (long)m * p.ldr + n), r);
+        load8f_nt(p.resid + (long)m * p.ldr + n, r);
 #pragma unroll
         for (int t = 0; t < 8; ++t) v[t] += r[t];
       } else if (EPI == EPI_ACTBWD) {
         float u[8];
-        unpack8f(*(const uint4 *)(p.aux + o), u);
+        load8f_nt(p.aux + o, u);
 #pragma unroll
         for (int t = 0; t < 8; ++t) v[t] *= p.act == SSDT_ACT_GELU ? gelu_grad_f(u[t]) : (u[t] > 0.f ? 1.f : 0.f);
       }
-      *(uint4 *)(p.C + o) = make_uint4(pack_bf2(v[0], v[1]), pack_bf2(v[2], v[3]), pack_bf2(v[4], v[5]), pack_bf2(v[6], v[7]));
+      store8_nt(p.C + o, v);
     }
   }
 }
