@@ -29,24 +29,27 @@ __device__ __forceinline__ void st(float *p, float x) { *p = x; }
 __device__ __forceinline__ void st(bf16 *p, float x) { p->v = f2bf(x); }
 
 // erf by the rational approximation 7.1.26 of Abramowitz & Stegun (absolute error below 1.5e-7):
-// a handful of FMAs, one reciprocal and one exponential, so that it can sit in a GEMM epilogue
-// without the register cost of the library routine.
-__device__ __forceinline__ float erf_as(float x) {
-  const float ax = fabsf(x);
-  const float t = __frcp_rn(fmaf(0.3275911f, ax, 1.f));
+// a handful of FMAs, one hardware reciprocal (v_rcp_f32, 1 ulp; a correctly rounded division would cost ten
+// instructions more per element of a GEMM epilogue) and one hardware exponential.
+// erf_core(x, e) returns erf(x) given e = exp(-x*x), so that callers that need the exponential too share it.
+__device__ __forceinline__ float erf_core(float x, float e) {
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, fabsf(x), 1.f));
   float poly = fmaf(1.061405429f, t, -1.453152027f);
   poly = fmaf(poly, t, 1.421413741f);
   poly = fmaf(poly, t, -0.284496736f);
   poly = fmaf(poly, t, 0.254829592f);
-  const float r = 1.f - poly * t * __expf(-ax * ax);
-  return copysignf(r, x);
+  return copysignf(fmaf(-poly * t, e, 1.f), x);
 }
-// GELU in its erf form and its derivative.
-__device__ __forceinline__ float gelu_f(float u) { return 0.5f * u * (1.f + erf_as(u * 0.70710678118654752f)); }
+// exp(-u*u/2) = 2^(-u*u * log2(e)/2)
+__device__ __forceinline__ float exp_mhalf_sq(float u) { return __builtin_amdgcn_exp2f(u * u * -0.72134752044448170f); }
+// GELU in its erf form and its derivative: cdf(u) = (1 + erf(u / sqrt 2)) / 2, pdf(u) = exp(-u*u/2) / sqrt(2 pi).
+__device__ __forceinline__ float gelu_f(float u) {
+  return 0.5f * u * (1.f + erf_core(u * 0.70710678118654752f, exp_mhalf_sq(u)));
+}
 __device__ __forceinline__ float gelu_grad_f(float u) {
-  float cdf = 0.5f * (1.f + erf_as(u * 0.70710678118654752f));
-  float pdf = __expf(-0.5f * u * u) * 0.39894228040143268f;
-  return cdf + u * pdf;
+  const float e = exp_mhalf_sq(u);
+  const float cdf = 0.5f * (1.f + erf_core(u * 0.70710678118654752f, e));
+  return fmaf(u * 0.39894228040143268f, e, cdf);
 }
 
 __device__ __forceinline__ float wave_sum(float v) {

@@ -143,8 +143,13 @@ __device__ __forceinline__ void epilogue_rows(const NtP &p, const float *st, int
     const long o = (long)m * p.ldc + n;
     if (EPI == EPI_BIAS_ACT) {
       if (p.C) store8_nt(p.C + o, v);
+      if (p.act == SSDT_ACT_GELU) {
 #pragma unroll
-      for (int t = 0; t < 8; ++t) v[t] = p.act == SSDT_ACT_GELU ? gelu_f(v[t]) : fmaxf(v[t], 0.f);
+        for (int t = 0; t < 8; ++t) v[t] = gelu_f(v[t]);
+      } else {
+#pragma unroll
+        for (int t = 0; t < 8; ++t) v[t] = fmaxf(v[t], 0.f);
+      }
       store8_nt(p.C2 + o, v);
     } else {
       if (EPI == EPI_BIAS_RESID) {
@@ -155,8 +160,13 @@ __device__ __forceinline__ void epilogue_rows(const NtP &p, const float *st, int
       } else if (EPI == EPI_ACTBWD) {
         float u[8];
         load8f_nt(p.aux + o, u);
+        if (p.act == SSDT_ACT_GELU) {
 #pragma unroll
-        for (int t = 0; t < 8; ++t) v[t] *= p.act == SSDT_ACT_GELU ? gelu_grad_f(u[t]) : (u[t] > 0.f ? 1.f : 0.f);
+          for (int t = 0; t < 8; ++t) v[t] *= gelu_grad_f(u[t]);
+        } else {
+#pragma unroll
+          for (int t = 0; t < 8; ++t) v[t] = u[t] > 0.f ? v[t] : 0.f;
+        }
       }
       store8_nt(p.C + o, v);
     }
