@@ -141,6 +141,10 @@ VARIANTS = {
     "bert_mfma": dict(arch="bert_postln", B=3, S=128, H=256, A=4, F=512, act="gelu", norm="layernorm", mask="keypad", has_bias=True, eps=1e-5),
     "t5enc_mfma": dict(arch="t5_enc", B=2, S=128, H=128, A=2, F=384, act="relu", norm="rmsnorm", mask="none", has_bias=False, eps=1e-6),
     "t5dec_mfma": dict(arch="t5_dec", B=2, S=128, S_kv=256, H=128, A=2, F=256, act="relu", norm="rmsnorm", mask="causal", has_bias=False, eps=1e-6),
+    # 4096 x 4096 outputs (256 tiles of 256 x 256: the large-tile GEMM kernel) over a contraction of only two
+    # and three 64-wide stages: its prologue and its peeled last stages without the steady-state loop between
+    "gpt_thin128": dict(arch="gpt_preln", B=2, S=2048, H=128, A=2, F=4096, act="gelu", norm="layernorm", mask="causal", has_bias=True, eps=1e-5),
+    "gpt_thin192": dict(arch="gpt_preln", B=2, S=2048, H=192, A=3, F=4096, act="gelu", norm="layernorm", mask="causal", has_bias=True, eps=1e-5),
 }
 
 
