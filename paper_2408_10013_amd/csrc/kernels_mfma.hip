@@ -544,8 +544,10 @@ hipError_t gemm_mfma_bf16(const Gemm &g, hipStream_t s) {
   p.tiles_m = g.M / t;
   p.tiles_n = g.N / t;
   // tile rows per group of the workgroup order: the 32 workgroups an XCD runs side by side then cover 4 x 8 or
-  // 8 x 4 tiles; measured 1-5 % apart on the layer's shapes, the better one depends on which extent is longer
-  p.gm = g_force_waves > 0 ? g_force_waves : (p.tiles_m >= p.tiles_n ? 4 : 8);
+  // 8 x 4 tiles; measured 1-5 % apart on the layer's shapes, the better one depends on which extent is longer,
+  // and on whether Bt's rows are a multiple of 32 KiB apart (a stored weight that cannot be padded: then fewer
+  // Bt panels side by side is better, 1311 -> 1372 TFLOP/s on 32768 x 8192 x 32768)
+  p.gm = g_force_waves > 0 ? g_force_waves : ((ldb * 2) % 32768 == 0 ? 8 : (p.tiles_m >= p.tiles_n ? 4 : 8));
   return launch_epi(big, g.epi, p, s);
 }
 
