@@ -153,40 +153,46 @@ __global__ __launch_bounds__(256, 2) void fa_fwd_k(FaP p) {
         bf16x8_t kf = *(const bf16x8_t *)(sK + (kb * 32 + li) * LK + ks * 16 + half * 8);
         sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc[kb], 0, 0, 0);
       }
-    // scale, mask, online softmax (this lane: query qi, keys j0 + kb*32 + (r/4)*8 + half*4 + r%4)
+    // mask, online softmax (this lane: query qi, keys j0 + kb*32 + (r/4)*8 + half*4 + r%4).  The running
+    // maximum m is kept in units of the raw scores; the softmax scale (positive) and log2(e) enter only through
+    // the exponent's fused multiply-add
     const bool need_mask = (p.mask == SSDT_MASK_CAUSAL && j0 + BKV - 1 > q0) || (j0 + BKV > limit);
+    if (need_mask) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = j0 + kb * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
+          if (key >= limit || (p.mask == SSDT_MASK_CAUSAL && key > qi)) sacc[kb][r] = -INFINITY;
+        }
+    }
     float mloc = -INFINITY;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float s = sacc[kb][r] * sc;
-        if (need_mask) {
-          int key = j0 + kb * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
-          if (key >= limit || (p.mask == SSDT_MASK_CAUSAL && key > qi)) s = -INFINITY;
-        }
-        sacc[kb][r] = s;
-        mloc = fmaxf(mloc, s);
-      }
+      for (int r = 0; r < 16; ++r) mloc = fmaxf(mloc, sacc[kb][r]);
     mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
-    const float mnew = fmaxf(m, mloc), msafe = (mnew == -INFINITY) ? 0.f : mnew;
-    const float corr = __builtin_amdgcn_exp2f(m - msafe);
+    const float mnew = fmaxf(m, mloc), moff = (mnew == -INFINITY) ? 0.f : -mnew * sc;
     float lsum = 0.f;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        float e = __builtin_amdgcn_exp2f(sacc[kb][r] - msafe);
+        const float e = __builtin_amdgcn_exp2f(fmaf(sacc[kb][r], sc, moff));
         sacc[kb][r] = e;
         lsum += e;
       }
     lsum += __shfl_xor(lsum, 32, 64);
-    l = l * corr + lsum;
-    m = mnew;
+    if (__builtin_amdgcn_ballot_w64(mnew != m) != 0) {  // some query's maximum moved: rescale what has been accumulated
+      const float corr = __builtin_amdgcn_exp2f(fmaf(m, sc, moff));
+      l *= corr;
 #pragma unroll
-    for (int d = 0; d < DB; ++d)
+      for (int d = 0; d < DB; ++d)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) oacc[d][r] *= corr;
+        for (int r = 0; r < 16; ++r) oacc[d][r] *= corr;
+      m = mnew;
+    }
+    l += lsum;
     // O^T += V^T P^T, 16 keys per step
 #pragma unroll
     for (int s4 = 0; s4 < 4; ++s4) {
@@ -211,12 +217,13 @@ __global__ __launch_bounds__(256, 2) void fa_fwd_k(FaP p) {
                            pack_bf2(oacc[d][g * 4 + 2] * inv, oacc[d][g * 4 + 3] * inv));
       *(uint2 *)(op + d * 32 + g * 8 + half * 4) = v;
     }
-  if (half == 0) p.lse[((long)b * p.A + h) * p.Sq + qi] = l > 0.f ? m * kLn2 + logf(l) : -INFINITY;
+  if (half == 0) p.lse[((long)b * p.A + h) * p.Sq + qi] = l > 0.f ? m * p.scale + logf(l) : -INFINITY;
 }
 
 static bool fa_supported(const Attn &a) {
   if (a.dtype != SSDT_BF16 || (a.d != 64 && a.d != 128)) return false;
   if (a.Sq % 128 || a.Sk % 128) return false;
+  if (!(a.scale > 0.f)) return false;  // the running maximum is taken on unscaled scores
   auto al = [](const void *p) { return ((uintptr_t)p & 15) == 0; };
   if (!al(a.q) || !al(a.k) || !al(a.v) || a.ldq % 8 || a.ldk % 8 || a.ldv % 8) return false;
   return true;
