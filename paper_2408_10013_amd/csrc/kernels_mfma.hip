@@ -222,8 +222,9 @@ __global__ __launch_bounds__(512) void gemm_nt256_k(NtP p) {
   // which holds global chunk (t%8) ^ ((row >> 1) & 7); 8 consecutive lanes fetch one 128-byte line.  A load is
   // `global_load_lds_dwordx4 voff, s[base]`: the base (tile and stage) sits in scalar registers and advances by
   // scalar adds, the per-lane part is a 32-bit byte offset that never changes; M0 (the LDS destination of the
-  // wavefront's 1 KiB) is set in the same statement.  No instruction offset on the load: it would be added
-  // to the LDS address as well as to the global one.
+  // wavefront's 1 KiB) is set in the same statement (M0 cannot be named as a clobber; nothing else in this kernel
+  // uses it: LDS instructions need no M0 here and there is no other direct-to-LDS load).  No instruction offset
+  // on the load: it would be added to the LDS address as well as to the global one.
   const int lrow = tid >> 3, lchunk = (tid & 7) ^ ((lrow >> 1) & 7);
   unsigned voa[LJ], vob[LJ];
 #pragma unroll
@@ -537,9 +538,11 @@ hipError_t gemm_mfma_bf16(const Gemm &g, hipStream_t s) {
         (const uint16_t *)g.resid, (const uint16_t *)g.aux, g.act, 0, 0, 8};
   const bool epi16 = g.ldc % 8 == 0 && al16(g.C) && (!g.C2 || al16(g.C2)) && (!g.bias || al16(g.bias)) &&
                      (!g.aux || al16(g.aux)) && (!g.resid || (al16(g.resid) && g.ldr % 8 == 0));
-  bool big = epi16 && (g.M % 256 == 0) && (g.N % 256 == 0) && ((long)(g.M / 256) * (g.N / 256) >= 256);
+  // the large-tile kernel addresses a tile's 256 rows with 32-bit byte offsets
+  const bool fits256 = epi16 && g.M % 256 == 0 && g.N % 256 == 0 && lda < (1L << 22) && ldb < (1L << 22);
+  bool big = fits256 && (long)(g.M / 256) * (g.N / 256) >= 256;
   if (g_force_tile == 128) big = false;
-  if (g_force_tile == 256 && epi16 && g.M % 256 == 0 && g.N % 256 == 0) big = true;
+  if (g_force_tile == 256 && fits256) big = true;
   const int t = big ? 256 : 128;
   p.tiles_m = g.M / t;
   p.tiles_n = g.N / t;
