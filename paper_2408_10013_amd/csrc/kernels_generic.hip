@@ -590,6 +590,7 @@ __global__ __launch_bounds__(256) void transpose_k(const U *in, long ldi, U *out
 // 16-byte accesses only and no LDS.  Lane (rb, cb) = (lane / 8, lane % 8) reads the 8x8 block at rows
 // 8 rb.., columns 8 cb.. (eight lanes cover one 128-byte line of each row), transposes it in registers and
 // writes it as rows 8 cb.., columns 8 rb.. of the output (again eight lanes per 128-byte line).
+typedef unsigned int u32x4_nt __attribute__((ext_vector_type(4)));
 __global__ __launch_bounds__(256) void transpose16_k(const uint16_t *in, long ldi, uint16_t *out, long ldo, int rows, int cols) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r0 = (blockIdx.y * 2 + (wave >> 1)) * 64, c0 = (blockIdx.x * 2 + (wave & 1)) * 64;
@@ -599,7 +600,7 @@ __global__ __launch_bounds__(256) void transpose16_k(const uint16_t *in, long ld
   uint32_t v[8][4];
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
-    const uint4 q = *(const uint4 *)(src + i * ldi);
+    const u32x4_nt q = __builtin_nontemporal_load((const u32x4_nt *)(src + i * ldi));
     v[i][0] = q.x; v[i][1] = q.y; v[i][2] = q.z; v[i][3] = q.w;
   }
   uint16_t *dst = out + (long)(c0 + cb * 8) * ldo + r0 + rb * 8;
@@ -611,7 +612,8 @@ __global__ __launch_bounds__(256) void transpose16_k(const uint16_t *in, long ld
       const uint32_t a = v[2 * k][j >> 1], b = v[2 * k + 1][j >> 1];
       o[k] = (j & 1) ? ((a >> 16) | (b & 0xffff0000u)) : ((a & 0xffffu) | (b << 16));
     }
-    *(uint4 *)(dst + j * ldo) = make_uint4(o[0], o[1], o[2], o[3]);
+    const u32x4_nt w = {o[0], o[1], o[2], o[3]};
+    __builtin_nontemporal_store(w, (u32x4_nt *)(dst + j * ldo));
   }
 }
 
