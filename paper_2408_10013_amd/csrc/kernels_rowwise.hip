@@ -147,6 +147,7 @@ __global__ __launch_bounds__(256) void norm_bwd_dx_vec_k(const uint16_t *dy, con
 
 // Stage 1 of a column reduction: block (cx, chunk) sums 512 columns over its chunk of rows, the 4
 // wavefronts taking every 4th row, then adds the 4 partial sums in a fixed order.
+typedef unsigned int u32x4_nt __attribute__((ext_vector_type(4)));
 template <bool NORM>
 __global__ __launch_bounds__(256) void colreduce1_vec_k(const uint16_t *a, long lda, const uint16_t *x, const float *mean,
                                                         const float *rstd, int kind, float *partial, int rows, int cols,
@@ -161,7 +162,9 @@ __global__ __launch_bounds__(256) void colreduce1_vec_k(const uint16_t *a, long 
   if (c0 < cols) {
     for (int r = r0 + w; r < r1; r += 4) {
       float v[8];
-      unpack8(*(const uint4 *)(a + (long)r * lda + c0), v);
+      // streamed once, and usually underneath a GEMM on the other stream: keep it out of the L2's way
+      const u32x4_nt q = __builtin_nontemporal_load((const u32x4_nt *)(a + (long)r * lda + c0));
+      unpack8(make_uint4(q.x, q.y, q.z, q.w), v);
 #pragma unroll
       for (int t = 0; t < 8; ++t) b[t] += v[t];
       if (NORM) {
