@@ -87,11 +87,15 @@ template <int NCH>
 __global__ __launch_bounds__(256) void norm_bwd_dx_vec_k(const uint16_t *dy, const uint16_t *x, const float *mean,
                                                          const float *rstd, const uint16_t *gamma, const uint16_t *resid,
                                                          uint16_t *dx, int rows, int H, int kind) {
+  // the gain vector is shared by the block's four rows and read twice per row: staged in LDS once (read from global
+  // memory chunk by chunk, every one of its 2 x NCH loads was a full round trip in front of the arithmetic)
+  __shared__ uint4 g4[NCH * 64];
   const int lane = threadIdx.x & 63, row = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (row >= rows) return;
   const int nch = H >> 3;
+  for (int c = threadIdx.x; c < nch; c += 256) g4[c] = ((const uint4 *)gamma)[c];
+  __syncthreads();
+  if (row >= rows) return;
   const uint4 *xr = (const uint4 *)(x + (long)row * H), *dyr = (const uint4 *)(dy + (long)row * H);
-  const uint4 *g4 = (const uint4 *)gamma;
   const float mu = (kind == SSDT_NORM_LAYERNORM) ? mean[row] : 0.f, r = rstd[row];
   uint4 vx[NCH], vd[NCH];
 #pragma unroll
@@ -120,7 +124,17 @@ __global__ __launch_bounds__(256) void norm_bwd_dx_vec_k(const uint16_t *dy, con
   const float c1 = (kind == SSDT_NORM_LAYERNORM) ? wave_sum(s1) / (float)H : 0.f;
   const float c2 = wave_sum(s2) / (float)H;
   uint4 *dxr = (uint4 *)(dx + (long)row * H);
-  const uint4 *rr = resid ? (const uint4 *)(resid + (long)row * H) : nullptr;
+  // the residual-branch gradient: all of its loads go out before the first result is stored (loads issued between
+  // stores are waited for one at a time, and this kernel is nothing but memory latency)
+  uint4 vr[NCH];
+  if (resid) {
+    const uint4 *rr = (const uint4 *)(resid + (long)row * H);
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const int c = i * 64 + lane;
+      vr[i] = c < nch ? rr[c] : make_uint4(0, 0, 0, 0);
+    }
+  }
 #pragma unroll
   for (int i = 0; i < NCH; ++i) {
     const int c = i * 64 + lane;
@@ -134,14 +148,19 @@ __global__ __launch_bounds__(256) void norm_bwd_dx_vec_k(const uint16_t *dy, con
         const float dh = fd[t] * g[t], xh = (fx[t] - mu) * r;
         o[t] = r * (dh - c1 - xh * c2);
       }
-      if (rr) {
+      if (resid) {
         float q[8];
-        unpack8(rr[c], q);
+        unpack8(vr[i], q);
 #pragma unroll
         for (int t = 0; t < 8; ++t) o[t] += q[t];
       }
-      dxr[c] = pack8(o);
+      vx[i] = pack8(o);
     }
+  }
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    const int c = i * 64 + lane;
+    if (c < nch) dxr[c] = vx[i];
   }
 }
 
