@@ -97,6 +97,10 @@ hipError_t attn_delta(const Attn &a, hipStream_t s);  // delta[b,h,i] = sum_c o[
 
 // out[c, r] = in[r, c]
 hipError_t transpose(const void *in, long ldi, void *out, long ldo, int rows, int cols, int dtype, hipStream_t s);
+// bf16 only: out[c, r] = in[r, c] and sums[c] (+)= sum_r in[r, c] in one pass over `in`; `partial` as for colsum.
+// hipErrorNotSupported (nothing launched) when the extents or alignments do not fit the kernel.
+hipError_t transpose_colsum(const void *in, long ldi, void *out, long ldo, int rows, int cols, void *sums, float *partial,
+                            bool accumulate, hipStream_t s);
 // y += x  (elementwise, n elements)
 hipError_t add_inplace(void *y, const void *x, size_t n, int dtype, hipStream_t s);
 

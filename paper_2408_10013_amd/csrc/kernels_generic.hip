@@ -617,6 +617,88 @@ __global__ __launch_bounds__(256) void transpose16_k(const uint16_t *in, long ld
   }
 }
 
+// The transposed copy and the column sums of a bf16 matrix in one pass over it (the weight-gradient product needs
+// dY transposed, the bias gradient is dY's column sums): a wavefront walks a 64-column strip of one row chunk in
+// 64x64 tiles, moving each tile as transpose16_k does and adding its rows into eight per-lane column sums; the next
+// tile's loads are issued before the current tile's stores, so that waiting for them never waits for a store.  At
+// the end the eight lanes that share a column block are added in a fixed order and the chunk's sums go to
+// partial[chunk][column] (stage 2 of the column reduction finishes the job).
+__global__ __launch_bounds__(256) void transpose_colsum16_k(const uint16_t *in, long ldi, uint16_t *out, long ldo, int rows,
+                                                            int cols, float *partial, int rows_per_chunk) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int c0 = (blockIdx.x * 4 + wave) * 64;
+  if (c0 >= cols) return;
+  const int rb = lane >> 3, cb = lane & 7;
+  const int r_begin = blockIdx.y * rows_per_chunk, r_end = min(rows, r_begin + rows_per_chunk);
+  float acc[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) acc[j] = 0.f;
+  u32x4_nt v[8], nv[8];
+  const uint16_t *src = in + (long)(r_begin + rb * 8) * ldi + c0 + cb * 8;
+  if (r_begin < r_end) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = __builtin_nontemporal_load((const u32x4_nt *)(src + i * ldi));
+  }
+  for (int r0 = r_begin; r0 < r_end; r0 += 64) {
+    src += 64 * ldi;
+    if (r0 + 64 < r_end) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) nv[i] = __builtin_nontemporal_load((const u32x4_nt *)(src + i * ldi));
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        acc[2 * k] += __uint_as_float(v[i][k] << 16);
+        acc[2 * k + 1] += __uint_as_float(v[i][k] & 0xffff0000u);
+      }
+    uint16_t *dst = out + (long)(c0 + cb * 8) * ldo + r0 + rb * 8;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      uint32_t o[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const uint32_t a = v[2 * k][j >> 1], b = v[2 * k + 1][j >> 1];
+        o[k] = (j & 1) ? ((a >> 16) | (b & 0xffff0000u)) : ((a & 0xffffu) | (b << 16));
+      }
+      const u32x4_nt w = {o[0], o[1], o[2], o[3]};
+      __builtin_nontemporal_store(w, (u32x4_nt *)(dst + j * ldo));
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = nv[i];
+  }
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    acc[j] += __shfl_xor(acc[j], 8, 64);
+    acc[j] += __shfl_xor(acc[j], 16, 64);
+    acc[j] += __shfl_xor(acc[j], 32, 64);
+  }
+  if (rb == 0) {
+    float *dst = partial + (size_t)blockIdx.y * cols + c0 + cb * 8;
+    *(float4 *)dst = make_float4(acc[0], acc[1], acc[2], acc[3]);
+    *(float4 *)(dst + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
+  }
+}
+
+hipError_t transpose_colsum(const void *in, long ldi, void *out, long ldo, int rows, int cols, void *sums, float *partial,
+                            bool accumulate, hipStream_t s) {
+  const int chunks = colreduce_chunks(rows);
+  if (rows % 64 || cols % 64 || ldi % 8 || ldo % 8 || ((uintptr_t)in | (uintptr_t)out | (uintptr_t)partial) % 16 || rows % chunks ||
+      (rows / chunks) % 64)
+    return hipErrorNotSupported;
+  {
+    prof::Scope ps(prof::TRANSPOSE, 0, 2.0 * rows * cols * 2, s);
+    hipLaunchKernelGGL(transpose_colsum16_k, dim3((cols / 64 + 3) / 4, chunks), dim3(256), 0, s, (const uint16_t *)in, ldi,
+                       (uint16_t *)out, ldo, rows, cols, partial, rows / chunks);
+    SSDT_LAUNCH_CHECK();
+  }
+  prof::Scope ps(prof::COLREDUCE, 0, 4.0 * chunks * cols, s);
+  hipLaunchKernelGGL(colreduce2_k<bf16>, dim3((cols + 255) / 256), dim3(256), 0, s, (const float *)partial, chunks, cols,
+                     (bf16 *)sums, (bf16 *)nullptr, accumulate ? 1 : 0);
+  SSDT_LAUNCH_CHECK();
+  return hipSuccess;
+}
+
 hipError_t transpose(const void *in, long ldi, void *out, long ldo, int rows, int cols, int dtype, hipStream_t s) {
   dim3 grid((cols + 63) / 64, (rows + 63) / 64);
   prof::Scope ps(prof::TRANSPOSE, 0, 2.0 * rows * cols * (dtype == SSDT_F32 ? 4 : 2), s);

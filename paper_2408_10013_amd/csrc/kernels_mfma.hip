@@ -121,15 +121,27 @@ __device__ __forceinline__ void store8_nt(uint16_t *dst, const float *v) {
   const u32x4_t q = {pack_bf2(v[0], v[1]), pack_bf2(v[2], v[3]), pack_bf2(v[4], v[5]), pack_bf2(v[6], v[7])};
   __builtin_nontemporal_store(q, (u32x4_t *)dst);
 }
-__device__ __forceinline__ void load8f_nt(const uint16_t *src, float *f) {
-  const u32x4_t q = __builtin_nontemporal_load((const u32x4_t *)src);
-  unpack8f(make_uint4(q.x, q.y, q.z, q.w), f);
+// The residual / activation-input rows of one 64x64 sub-tile (eight row passes), fetched before anything is
+// stored: a load issued after a store is waited for together with that store (loads and stores share one
+// in-order counter), which made every row pass of those epilogues a full round trip.
+template <int EPI>
+__device__ __forceinline__ void epilogue_fetch(const NtP &p, int m_base, int n_base, int lane, u32x4_t (&in)[8]) {
+  if (EPI != EPI_BIAS_RESID && EPI != EPI_ACTBWD) return;
+  const int n = n_base + (lane & 7) * 8;
+#pragma unroll
+  for (int pass = 0; pass < 8; ++pass) {
+    const int m = m_base + pass * 8 + (lane >> 3);
+    const uint16_t *src = EPI == EPI_BIAS_RESID ? p.resid + (long)m * p.ldr + n : p.aux + (long)m * p.ldc + n;
+    in[pass] = __builtin_nontemporal_load((const u32x4_t *)src);
+  }
 }
 
 // Second half of the staged epilogue: a 64x64 fp32 sub-tile sits row-major (leading dimension kEpiLd) in this
-// wavefront's staging area `st`; apply the epilogue and store it, 16 bytes per lane per access.
+// wavefront's staging area `st`; apply the epilogue (inputs already in `in`) and store it, 16 bytes per lane per
+// access.
 template <int EPI>
-__device__ __forceinline__ void epilogue_rows(const NtP &p, const float *st, int m_base, int n_base, int lane) {
+__device__ __forceinline__ void epilogue_rows(const NtP &p, const float *st, int m_base, int n_base, int lane,
+                                              const u32x4_t (&in)[8]) {
   const int col0 = (lane & 7) * 8, n = n_base + col0;
   float b[8];
 #pragma unroll
@@ -154,12 +166,12 @@ __device__ __forceinline__ void epilogue_rows(const NtP &p, const float *st, int
     } else {
       if (EPI == EPI_BIAS_RESID) {
         float r[8];
-        load8f_nt(p.resid + (long)m * p.ldr + n, r);
+        unpack8f(make_uint4(in[pass].x, in[pass].y, in[pass].z, in[pass].w), r);
 #pragma unroll
         for (int t = 0; t < 8; ++t) v[t] += r[t];
       } else if (EPI == EPI_ACTBWD) {
         float u[8];
-        load8f_nt(p.aux + o, u);
+        unpack8f(make_uint4(in[pass].x, in[pass].y, in[pass].z, in[pass].w), u);
         if (p.act == SSDT_ACT_GELU) {
 #pragma unroll
           for (int t = 0; t < 8; ++t) v[t] *= gelu_grad_f(u[t]);
@@ -353,6 +365,9 @@ __global__ __launch_bounds__(512) void gemm_nt256_k(NtP p) {
 #undef SSDT_STAGE
   // epilogue through LDS (free now), two 64x64 sub-tiles of the wavefront's 128x64: lane l of block (i, j) holds
   // row i*16 + (l & 15), columns j*16 + (l >> 4)*4 + 0..3
+  u32x4_t ein[MB / 4][8];  // residual / activation-input rows of both sub-tiles, on their way before the first store
+#pragma unroll
+  for (int I = 0; I < MB / 4; ++I) epilogue_fetch<EPI>(p, m0 + wm * 128 + I * 64, n0 + wn * 64, lane, ein[I]);
   __builtin_amdgcn_s_barrier();  // every wavefront has finished reading the last stage
   float *stg = (float *)smem + wave * (64 * kEpiLd);
 #pragma unroll
@@ -364,7 +379,7 @@ __global__ __launch_bounds__(512) void gemm_nt256_k(NtP p) {
         const f32x4_t a = acc[I * 4 + il][jl];
         *(float4 *)(stg + (il * 16 + lr) * kEpiLd + jl * 16 + lq * 4) = make_float4(a[0], a[1], a[2], a[3]);
       }
-    epilogue_rows<EPI>(p, stg, m0 + wm * 128 + I * 64, n0 + wn * 64, lane);
+    epilogue_rows<EPI>(p, stg, m0 + wm * 128 + I * 64, n0 + wn * 64, lane, ein[I]);
   }
 }
 

@@ -403,8 +403,15 @@ ssdt_status ssdt_layer_bwd(ssdt_ctx *ctx, const ssdt_layer_desc *desc, const ssd
     drop(ctx->be.get(), go);
     uint16_t *At = (uint16_t *)bf.scratch, *Bt = (uint16_t *)((char *)bf.scratch + a_bytes);
     hipError_t e1 = k::transpose(in, Kin, At, ld, rows, Kin, SSDT_BF16, side);     // [rows, Kin] -> [Kin, rows]
-    if (e1 == hipSuccess) e1 = k::transpose(dY, Nout, Bt, ld, rows, Nout, SSDT_BF16, side);  // [rows, Nout] -> [Nout, rows]
-    if (e1 == hipSuccess && db) e1 = k::colsum(dY, Nout, db, bf.partial_side, rows, Nout, dt, accum, side);
+    // [rows, Nout] -> [Nout, rows], with the bias gradient taken from the same pass over dY where the kernel fits
+    hipError_t e2 = e1 != hipSuccess ? e1 : db ? k::transpose_colsum(dY, Nout, Bt, ld, rows, Nout, db, bf.partial_side, accum, side)
+                                               : hipErrorNotSupported;
+    if (e2 == hipErrorNotSupported) {
+      e1 = k::transpose(dY, Nout, Bt, ld, rows, Nout, SSDT_BF16, side);
+      if (e1 == hipSuccess && db) e1 = k::colsum(dY, Nout, db, bf.partial_side, rows, Nout, dt, accum, side);
+    } else {
+      e1 = e2;
+    }
     if (e1 != hipSuccess) return e1;
     pend.on = true; pend.Kin = Kin; pend.Nout = Nout; pend.rows = rows; pend.ld = ld; pend.dW = dW; pend.At = At; pend.Bt = Bt;
     pend.ready = hold(ctx->be->record(side, false));
