@@ -59,6 +59,14 @@ __device__ __forceinline__ bf16x8_t pack8(const float *a, const float *b) {
   return u.v;
 }
 
+// Swizzle key of row r of an unpadded tile with 256-byte rows (128 bf16): 16-byte chunk c of the row is stored at
+// chunk position c ^ swz(r).  The key is r's low four bits with the two bit pairs swapped.  Any bijection of those
+// bits makes the row-fragment reads conflict-free (16 consecutive rows, same logical chunk: 16 distinct positions);
+// this one also spreads the transposing reads, whose 32 lanes take a window of 4 consecutive k-rows x 64 bytes:
+// r's two low bits land in the chunk's two high bits, so the four rows of a window sit in the four different
+// 64-byte bank groups (with the plain key r & 15 they shared one and every such read took four passes).
+__device__ __forceinline__ int swz(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
+
 // copies ROWS x D bf16 (row stride ld in global memory) into LDS with row stride LDS_LD; rows at or
 // beyond `valid` are zero-filled
 template <int D, int ROWS, int LDS_LD>
@@ -95,12 +103,24 @@ __device__ __forceinline__ void tile_sstore(uint16_t *s, int tid, const uint4 (&
   }
 }
 
+// tile_sstore into a swizzled tile with 128-element rows
+template <int ROWS>
+__device__ __forceinline__ void tile_sstore_sw(uint16_t *s, int tid, const uint4 (&r)[ROWS * 16 / 256]) {
+#pragma unroll
+  for (int i = 0; i < ROWS * 16 / 256; ++i) {
+    const int c = tid + i * 256, row = c >> 4, kc = c & 15;
+    *(uint4 *)(s + row * 128 + ((kc ^ swz(row)) << 3)) = r[i];
+  }
+}
+
 // ------------------------------------------------------------------------------------------
 // forward: one workgroup = 128 queries of one (sequence, head); each wavefront 32 queries
 // ------------------------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(256, 2) void fa_fwd_k(FaP p) {
-  constexpr int BKV = 64, LK = D + 8, LV = D + 16, KS = D / 16, DB = D / 32;
+  // V is only ever read through the transposing reads (windows of 4 k-rows x 64 bytes per 32 lanes): a row stride
+  // of 64 bytes modulo 256 puts the four rows of a window into four different bank groups
+  constexpr int BKV = 64, LK = D + 8, LV = D + 32, KS = D / 16, DB = D / 32;
   __shared__ __attribute__((aligned(16))) uint16_t sK[BKV * LK];
   __shared__ __attribute__((aligned(16))) uint16_t sV[BKV * LV];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, half = lane >> 5, li = lane & 31;
@@ -394,14 +414,14 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dkv_k(FaP p) {
 // its time, and prefetching through registers does not fit beside the 128 accumulator registers at two
 // wavefronts per SIMD.  Here the tiles are 32 queries, double-buffered in LDS and filled by direct
 // global-to-LDS loads issued one tile ahead (no registers), V rows live in LDS, and rows are unpadded 256-byte
-// lines whose 16-byte chunk index is XOR-ed with (row & 15) so that both the row-fragment reads and the
+// lines whose 16-byte chunk index is XOR-ed with swz(row) so that both the row-fragment reads and the
 // transposing reads are free of bank conflicts.  The two tile buffers are separate arrays and the loop is
 // unrolled by two, so that the compiler can see that a load in flight never targets the buffer being read.
 // ------------------------------------------------------------------------------------------
 typedef __attribute__((address_space(3))) void lds_void_t;
 
 // element offset of 16-byte chunk c of row r in a swizzled tile with 128-element rows
-__device__ __forceinline__ int sw128(int r, int c) { return r * 128 + ((c ^ (r & 15)) << 3); }
+__device__ __forceinline__ int sw128(int r, int c) { return r * 128 + ((c ^ swz(r)) << 3); }
 
 // ROWS x 128 bf16 from global rows (stride ld) into a swizzled LDS tile by direct loads: one wavefront
 // instruction moves four rows; wavefront w of four takes rows 16 j + 4 w .. + 3 of every group of 16
@@ -413,7 +433,7 @@ __device__ __forceinline__ void dma_tile128(const uint16_t *g, int ld, uint16_t 
 #pragma unroll
   for (int j = 0; j < ROWS / 16; ++j) {
     const int r0 = j * 16 + w * 4, r = r0 + (lane >> 4), c = lane & 15;
-    const unsigned off = (unsigned)(r * ld + ((c ^ (r & 15)) << 3));
+    const unsigned off = (unsigned)(r * ld + ((c ^ swz(r)) << 3));
     __builtin_amdgcn_global_load_lds(g + off, (lds_void_t *)(s + r0 * 128), 16, 0, 0);
   }
 }
@@ -429,8 +449,9 @@ __device__ __forceinline__ void dkv128_tile(const FaP &p, const uint16_t *sQ, co
   if (p.mask == SSDT_MASK_CAUSAL && i0 + 31 < k0) return;  // every query of the tile precedes this wavefront's keys
   const bool need_mask = (p.mask == SSDT_MASK_CAUSAL && i0 < k0 + 31) || (k0 + 32 > limit);
   const float sc = p.scale * kLog2e;
-  // row fragments: row li, chunk (2 ks + half) ^ (li & 15)  ->  base ^ (ks << 4) elements
-  int rbase = li * 128 + (((half ^ li) & 1) << 3) + (((li & 15) >> 1) << 4);
+  // row fragments: row li, chunk (2 ks + half) ^ swz(li)  ->  base ^ (ks << 4) elements
+  const int sl = swz(li);
+  int rbase = li * 128 + (((half ^ sl) & 1) << 3) + ((sl >> 1) << 4);
   asm volatile("" : "+v"(rbase));
   const int vbase = rbase + w * 32 * 128;
   f32x16_t sacc, dpacc;
@@ -465,10 +486,11 @@ __device__ __forceinline__ void dkv128_tile(const FaP &p, const uint16_t *sQ, co
   }
   // transposing reads (see frag_tr): lane L of a group of 16 supplies the 4 elements at k-row (k + L/4), columns
   // c0 + 4 (L % 4) ..., and receives column c0 + L, k-rows k .. k+3.  k-rows used: 16 gs + 4 half (+ 8) + L/4;
-  // the swizzle term of such a row is 4 half (+ 8) + L/4, so the offset for column block d is base ^ (d << 5).
+  // the swizzle key of such a row is swz(4 half (+ 8) + L/4), a constant of the lane, so the offset for column block d
+  // is base ^ (d << 5).
   const int L = lane & 15, kr = L >> 2, g1 = (lane >> 4) & 1, lowc = g1 * 2 + ((L & 3) >> 1);
-  int t0 = (half * 4 + kr) * 128 + ((lowc ^ (half * 4 + kr)) << 3) + (L & 1) * 4;
-  int t1 = (half * 4 + 8 + kr) * 128 + ((lowc ^ (half * 4 + 8 + kr)) << 3) + (L & 1) * 4;
+  int t0 = (half * 4 + kr) * 128 + ((lowc ^ swz(half * 4 + kr)) << 3) + (L & 1) * 4;
+  int t1 = (half * 4 + 8 + kr) * 128 + ((lowc ^ swz(half * 4 + 8 + kr)) << 3) + (L & 1) * 4;
   asm volatile("" : "+v"(t0), "+v"(t1));
 #pragma unroll
   for (int gs = 0; gs < 2; ++gs) {
@@ -567,8 +589,11 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dkv128_k(FaP p) {
 // ------------------------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(256, 2) void fa_bwd_dq_k(FaP p) {
+  // K is read both as row fragments and through the transposing reads: at head size 128 its tile is unpadded and
+  // swizzled (see swz); V is read as row fragments only and keeps the padded rows
   constexpr int BKV = 64, LK = D + 8, KS = D / 16, DB = D / 32;
-  __shared__ __attribute__((aligned(16))) uint16_t sK[BKV * LK];
+  constexpr bool SW = D == 128;
+  __shared__ __attribute__((aligned(16))) uint16_t sK[BKV * (SW ? D : LK)];
   __shared__ __attribute__((aligned(16))) uint16_t sV[BKV * LK];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, half = lane >> 5, li = lane & 31;
   const int nqb = p.Sq / 128;
@@ -606,7 +631,8 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dq_k(FaP p) {
   for (int t = 0; t < ntiles; ++t) {
     const int j0 = t * BKV;
     __syncthreads();
-    tile_sstore<D, BKV, LK>(sK, tid, rk);
+    if constexpr (SW) tile_sstore_sw<BKV>(sK, tid, rk);
+    else tile_sstore<D, BKV, LK>(sK, tid, rk);
     tile_sstore<D, BKV, LK>(sV, tid, rv);
     __syncthreads();
     if (t + 1 < ntiles) {
@@ -615,6 +641,13 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dq_k(FaP p) {
     }
     if (p.mask == SSDT_MASK_CAUSAL && j0 > q0 + 31) continue;
     const bool need_mask = (p.mask == SSDT_MASK_CAUSAL && j0 + BKV - 1 > q0) || (j0 + BKV > limit);
+    // swizzled K tile: per-lane bases that the step / column-block index is XOR-ed into (as in dkv128_tile; the
+    // empty asm keeps the derived addresses from being hoisted out of the tile loop into long-lived registers)
+    const int sl = swz(li), L = lane & 15, kr = L >> 2, lowc = ((lane >> 4) & 1) * 2 + ((L & 3) >> 1);
+    int rbase = li * 128 + (((half ^ sl) & 1) << 3) + ((sl >> 1) << 4);
+    int t0 = (half * 4 + kr) * 128 + ((lowc ^ swz(half * 4 + kr)) << 3) + (L & 1) * 4;
+    int t1 = (half * 4 + 8 + kr) * 128 + ((lowc ^ swz(half * 4 + 8 + kr)) << 3) + (L & 1) * 4;
+    asm volatile("" : "+v"(rbase), "+v"(t0), "+v"(t1));
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
       f32x16_t sacc, dpacc;
@@ -622,7 +655,8 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dq_k(FaP p) {
       for (int r = 0; r < 16; ++r) { sacc[r] = 0.f; dpacc[r] = 0.f; }
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        bf16x8_t ka = *(const bf16x8_t *)(sK + (kb * 32 + li) * LK + ks * 16 + half * 8);
+        bf16x8_t ka = SW ? *(const bf16x8_t *)(sK + kb * 32 * 128 + (rbase ^ (ks << 4)))
+                         : *(const bf16x8_t *)(sK + (kb * 32 + li) * LK + ks * 16 + half * 8);
         bf16x8_t va = *(const bf16x8_t *)(sV + (kb * 32 + li) * LK + ks * 16 + half * 8);
         sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[ks], sacc, 0, 0, 0);
         dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, dof[ks], dpacc, 0, 0, 0);
@@ -645,7 +679,16 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dq_k(FaP p) {
         const int klo = kb * 32 + gs * 16 + half * 4;
 #pragma unroll
         for (int d = 0; d < DB; ++d) {
-          bf16x8_t kt = frag_tr(sK, LK, klo, klo + 8, d * 32, lane);
+          bf16x8_t kt;
+          if constexpr (SW) {
+            union { struct { s16x4_t a, b; } s; bf16x8_t v; } u;
+            const uint16_t *tb = sK + (kb * 32 + gs * 16) * 128;
+            u.s.a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)(tb + (t0 ^ (d << 5))));
+            u.s.b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)(tb + (t1 ^ (d << 5))));
+            kt = u.v;
+          } else {
+            kt = frag_tr(sK, LK, klo, klo + 8, d * 32, lane);
+          }
           dqacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kt, dsf, dqacc[d], 0, 0, 0);
         }
       }
