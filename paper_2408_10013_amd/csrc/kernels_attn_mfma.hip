@@ -113,6 +113,26 @@ __device__ __forceinline__ void tile_sstore_sw(uint16_t *s, int tid, const uint4
   }
 }
 
+// Workgroups are handed to the eight XCDs round-robin in launch order, and each XCD has its own L2.  The blocks
+// of one (sequence, head) all walk the same K/V (or Q/dO) rows, so they should share an L2: the launch-order index L
+// is re-read as XCD L % 8, slot L / 8; the slots of an XCD walk the blocks of one head after the other, and the
+// heads are dealt to the XCDs round-robin (head g runs on XCD g % 8), so that the sequences of a batch, which may
+// differ in length, are spread over all of them.  Returns the (x, y, z) block index this workgroup works on.
+// (Measured at 64 heads, S 2048, head size 128, causal: forward 0.67 -> 0.48 ms, backward 2.20 -> 1.82 ms.)
+__device__ __forceinline__ void xcd_block(int *bx, int *by, int *bz) {
+  const int nx = gridDim.x, ny = gridDim.y, heads = ny * (int)gridDim.z;
+  const int L = blockIdx.x + nx * (blockIdx.y + ny * blockIdx.z);
+  int x = L % nx, g = L / nx;
+  if ((heads & 7) == 0) {
+    const int slot = L >> 3;
+    x = slot % nx;
+    g = (slot / nx) * 8 + (L & 7);
+  }
+  *bx = x;
+  *by = g % ny;
+  *bz = g / ny;
+}
+
 // ------------------------------------------------------------------------------------------
 // forward: one workgroup = 128 queries of one (sequence, head); each wavefront 32 queries
 // ------------------------------------------------------------------------------------------
@@ -125,8 +145,9 @@ __global__ __launch_bounds__(256, 2) void fa_fwd_k(FaP p) {
   __shared__ __attribute__((aligned(16))) uint16_t sV[BKV * LV];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, half = lane >> 5, li = lane & 31;
   const int nqb = p.Sq / 128;
-  const int qb = (p.mask == SSDT_MASK_CAUSAL) ? nqb - 1 - (int)blockIdx.x : (int)blockIdx.x;  // long rows first
-  const int h = blockIdx.y, b = blockIdx.z;
+  int bx, h, b;
+  xcd_block(&bx, &h, &b);
+  const int qb = (p.mask == SSDT_MASK_CAUSAL) ? nqb - 1 - bx : bx;  // long rows first
   const int q0 = qb * 128 + w * 32, qi = q0 + li;
   const uint16_t *qp = p.q + (long)(b * p.Sq + qi) * p.ldq + h * D;
   bf16x8_t qf[KS];
@@ -291,8 +312,9 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dkv_k(FaP p) {
   __shared__ __attribute__((aligned(16))) uint16_t sdO[BQ * LQ];
   __shared__ __attribute__((aligned(16))) float sLse[BQ], sDelta[BQ];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, half = lane >> 5, li = lane & 31;
-  const int h = blockIdx.y, b = blockIdx.z;
-  const int k0 = blockIdx.x * 128 + w * 32, kj = k0 + li;
+  int bx, h, b;
+  xcd_block(&bx, &h, &b);
+  const int k0 = bx * 128 + w * 32, kj = k0 + li;
   int limit = p.Sk;
   if (p.mask == SSDT_MASK_KEYPAD) limit = min(limit, max(0, p.kv_len[b]));
   const uint16_t *kp = p.k + (long)(b * p.Sk + kj) * p.ldk + h * D, *vp = p.v + (long)(b * p.Sk + kj) * p.ldv + h * D;
@@ -302,7 +324,7 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dkv_k(FaP p) {
     kf[ks] = *(const bf16x8_t *)(kp + ks * 16 + half * 8);
     if (!LEAN) vf[ks] = *(const bf16x8_t *)(vp + ks * 16 + half * 8);
   }
-  if (LEAN) load_tile<D, 128, LQ>(p.v + (long)(b * p.Sk + blockIdx.x * 128) * p.ldv + h * D, p.ldv, 128, sV, tid);
+  if (LEAN) load_tile<D, 128, LQ>(p.v + (long)(b * p.Sk + bx * 128) * p.ldv + h * D, p.ldv, 128, sV, tid);
   const uint16_t *vrow = sV + (w * 32 + li) * LQ + half * 8;  // this lane's V row (lean variant)
   f32x16_t dkacc[DB], dvacc[DB];
 #pragma unroll
@@ -313,8 +335,8 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dkv_k(FaP p) {
   const uint16_t *qg = p.q + (long)b * p.Sq * p.ldq + h * D, *dog = p.dout + (long)b * p.Sq * p.lddo + h * D;
   const float *lse_g = p.lse + ((long)b * p.A + h) * p.Sq, *delta_g = p.delta + ((long)b * p.A + h) * p.Sq;
   const int nt = p.Sq / BQ;
-  const int t0 = (p.mask == SSDT_MASK_CAUSAL) ? (int)(blockIdx.x * 128) / BQ : 0;
-  const bool block_live = (int)(blockIdx.x * 128) < limit;
+  const int t0 = (p.mask == SSDT_MASK_CAUSAL) ? (bx * 128) / BQ : 0;
+  const bool block_live = bx * 128 < limit;
 
   const int tstart = block_live ? t0 : nt;
   uint4 rq[BQ * (D / 8) / 256], rdo[BQ * (D / 8) / 256];
@@ -516,8 +538,9 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dkv128_k(FaP p) {
   __shared__ __attribute__((aligned(1024))) uint16_t sQ0[BQ * D], sdO0[BQ * D], sQ1[BQ * D], sdO1[BQ * D];
   __shared__ __attribute__((aligned(16))) float sLse0[BQ], sDelta0[BQ], sLse1[BQ], sDelta1[BQ];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, half = lane >> 5, li = lane & 31;
-  const int h = blockIdx.y, b = blockIdx.z;
-  const int kblock = blockIdx.x * 128, k0 = kblock + w * 32, kj = k0 + li;
+  int bx, h, b;
+  xcd_block(&bx, &h, &b);
+  const int kblock = bx * 128, k0 = kblock + w * 32, kj = k0 + li;
   int limit = p.Sk;
   if (p.mask == SSDT_MASK_KEYPAD) limit = min(limit, max(0, p.kv_len[b]));
   const uint16_t *kp = p.k + (long)(b * p.Sk + kj) * p.ldk + h * D;
@@ -597,8 +620,9 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dq_k(FaP p) {
   __shared__ __attribute__((aligned(16))) uint16_t sV[BKV * LK];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, half = lane >> 5, li = lane & 31;
   const int nqb = p.Sq / 128;
-  const int qb = (p.mask == SSDT_MASK_CAUSAL) ? nqb - 1 - (int)blockIdx.x : (int)blockIdx.x;
-  const int h = blockIdx.y, b = blockIdx.z;
+  int bx, h, b;
+  xcd_block(&bx, &h, &b);
+  const int qb = (p.mask == SSDT_MASK_CAUSAL) ? nqb - 1 - bx : bx;
   const int q0 = qb * 128 + w * 32, qi = q0 + li;
   const uint16_t *qp = p.q + (long)(b * p.Sq + qi) * p.ldq + h * D, *dop = p.dout + (long)(b * p.Sq + qi) * p.lddo + h * D;
   bf16x8_t qf[KS], dof[KS];
