@@ -194,8 +194,8 @@ __global__ __launch_bounds__(256, 2) void fa_fwd_k(FaP p) {
         bf16x8_t kf = *(const bf16x8_t *)(sK + (kb * 32 + li) * LK + ks * 16 + half * 8);
         sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc[kb], 0, 0, 0);
       }
-    // mask, online softmax (this lane: query qi, keys j0 + kb*32 + (r/4)*8 + half*4 + r%4).  The running
-    // maximum m is kept in units of the raw scores; the softmax scale (positive) and log2(e) enter only through
+    // mask, online softmax (this lane: query qi, keys j0 + kb*32 + (r/4)*8 + half*4 + r%4).  The reference
+    // point m is kept in units of the raw scores; the softmax scale (positive) and log2(e) enter only through
     // the exponent's fused multiply-add
     const bool need_mask = (p.mask == SSDT_MASK_CAUSAL && j0 + BKV - 1 > q0) || (j0 + BKV > limit);
     if (need_mask) {
@@ -213,7 +213,15 @@ __global__ __launch_bounds__(256, 2) void fa_fwd_k(FaP p) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) mloc = fmaxf(mloc, sacc[kb][r]);
     mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
-    const float mnew = fmaxf(m, mloc), moff = (mnew == -INFINITY) ? 0.f : -mnew * sc;
+    // The reference point m of the exponentials follows the running maximum lazily: it moves (and what has been
+    // accumulated is rescaled) only when some query's maximum has outgrown it by more than 2^kLazy, so exponentials
+    // stay below 2^kLazy and, once the first tiles are through, almost no tile pays for a rescale.  The shift
+    // cancels in o = acc / l and in lse = m scale + log l.  (On the first live tile m is -inf: the difference is +inf
+    // and the point moves; while everything is masked the difference is NaN and it does not.)
+    constexpr float kLazy = 8.f;
+    const float mnew = fmaxf(m, mloc);
+    const bool move = __builtin_amdgcn_ballot_w64((mnew - m) * sc > kLazy) != 0;  // uniform over the wavefront
+    const float mref = move ? mnew : m, moff = (mref == -INFINITY) ? 0.f : -mref * sc;
     float lsum = 0.f;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
@@ -224,7 +232,7 @@ __global__ __launch_bounds__(256, 2) void fa_fwd_k(FaP p) {
         lsum += e;
       }
     lsum += __shfl_xor(lsum, 32, 64);
-    if (__builtin_amdgcn_ballot_w64(mnew != m) != 0) {  // some query's maximum moved: rescale what has been accumulated
+    if (move) {
       const float corr = __builtin_amdgcn_exp2f(fmaf(m, sc, moff));
       l *= corr;
 #pragma unroll
