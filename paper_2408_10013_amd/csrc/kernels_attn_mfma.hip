@@ -544,7 +544,7 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dkv128_k(FaP p) {
   constexpr int D = 128, BQ = 32;
   __shared__ __attribute__((aligned(1024))) uint16_t sV[128 * D];
   __shared__ __attribute__((aligned(1024))) uint16_t sQ0[BQ * D], sdO0[BQ * D], sQ1[BQ * D], sdO1[BQ * D];
-  __shared__ __attribute__((aligned(16))) float sLse0[BQ], sDelta0[BQ], sLse1[BQ], sDelta1[BQ];
+  __shared__ __attribute__((aligned(256))) float sStat0[2 * BQ], sStat1[2 * BQ];  // lse of the tile's queries, then delta
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, half = lane >> 5, li = lane & 31;
   int bx, h, b;
   xcd_block(&bx, &h, &b);
@@ -564,42 +564,38 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dkv128_k(FaP p) {
   const float *lse_g = p.lse + ((long)b * p.A + h) * p.Sq, *delta_g = p.delta + ((long)b * p.A + h) * p.Sq;
   const int nt = p.Sq / BQ;
   const int tstart = kblock < limit ? (p.mask == SSDT_MASK_CAUSAL ? kblock / BQ : 0) : nt;
+  // the 32 lse and 32 delta values of a query tile travel like the tile itself: one direct-to-LDS load of 4 bytes per
+  // lane, issued by wavefront 0 with the tile's other loads and waited for with them
+  const float *stat_g = (lane < BQ ? lse_g : delta_g - BQ) + lane;
+  auto dma_stat = [&](int tile, float *dst) {
+    if (w == 0) __builtin_amdgcn_global_load_lds(stat_g + tile * BQ, (lds_void_t *)dst, 4, 0, 0);
+  };
 
   if (tstart < nt) {
     dma_tile128<128>(p.v + (long)(b * p.Sk + kblock) * p.ldv + h * D, (int)p.ldv, sV, w, lane);
     dma_tile128<BQ>(qg + (long)tstart * BQ * p.ldq, (int)p.ldq, sQ0, w, lane);
     dma_tile128<BQ>(dog + (long)tstart * BQ * p.lddo, (int)p.lddo, sdO0, w, lane);
-    if (tid < BQ) sLse0[tid] = lse_g[tstart * BQ + tid];
-    else if (tid < 2 * BQ) sDelta0[tid - BQ] = delta_g[tstart * BQ + tid - BQ];
+    dma_stat(tstart, sStat0);
   }
   // tile t sits in buffer (t - tstart) & 1; while it is consumed, tile t+1 loads into the other buffer
   for (int t = tstart; t < nt; t += 2) {
     __builtin_amdgcn_s_waitcnt(0xF70);  // vmcnt(0): this wavefront's loads of tile t have landed
     __syncthreads();                    // everyone's have, and everyone is done with the other buffer
-    float rstat = 0.f;
     if (t + 1 < nt) {
       dma_tile128<BQ>(qg + (long)(t + 1) * BQ * p.ldq, (int)p.ldq, sQ1, w, lane);
       dma_tile128<BQ>(dog + (long)(t + 1) * BQ * p.lddo, (int)p.lddo, sdO1, w, lane);
-      if (tid < BQ) rstat = lse_g[(t + 1) * BQ + tid];
-      else if (tid < 2 * BQ) rstat = delta_g[(t + 1) * BQ + tid - BQ];
+      dma_stat(t + 1, sStat1);
     }
-    dkv128_tile(p, sQ0, sdO0, sV, sLse0, sDelta0, kf, dkacc, dvacc, t * BQ, k0, limit, w, lane);
+    dkv128_tile(p, sQ0, sdO0, sV, sStat0, sStat0 + BQ, kf, dkacc, dvacc, t * BQ, k0, limit, w, lane);
     if (t + 1 >= nt) break;
-    if (tid < BQ) sLse1[tid] = rstat;
-    else if (tid < 2 * BQ) sDelta1[tid - BQ] = rstat;
     __builtin_amdgcn_s_waitcnt(0xF70);
     __syncthreads();
     if (t + 2 < nt) {
       dma_tile128<BQ>(qg + (long)(t + 2) * BQ * p.ldq, (int)p.ldq, sQ0, w, lane);
       dma_tile128<BQ>(dog + (long)(t + 2) * BQ * p.lddo, (int)p.lddo, sdO0, w, lane);
-      if (tid < BQ) rstat = lse_g[(t + 2) * BQ + tid];
-      else if (tid < 2 * BQ) rstat = delta_g[(t + 2) * BQ + tid - BQ];
+      dma_stat(t + 2, sStat0);
     }
-    dkv128_tile(p, sQ1, sdO1, sV, sLse1, sDelta1, kf, dkacc, dvacc, (t + 1) * BQ, k0, limit, w, lane);
-    if (t + 2 < nt) {
-      if (tid < BQ) sLse0[tid] = rstat;
-      else if (tid < 2 * BQ) sDelta0[tid - BQ] = rstat;
-    }
+    dkv128_tile(p, sQ1, sdO1, sV, sStat1, sStat1 + BQ, kf, dkacc, dvacc, (t + 1) * BQ, k0, limit, w, lane);
   }
   uint16_t *dkp = p.dk + (long)(b * p.Sk + kj) * p.lddk + h * D, *dvp = p.dv + (long)(b * p.Sk + kj) * p.lddv + h * D;
 #pragma unroll
