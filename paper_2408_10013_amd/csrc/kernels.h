@@ -109,6 +109,8 @@ hipError_t norm_fwd_vec(const void *x, const void *gamma, const void *beta, void
                         int H, float eps, int kind, hipStream_t s);
 hipError_t norm_bwd_dx_vec(const void *dy, const void *x, const float *mean, const float *rstd, const void *gamma,
                            const void *resid, void *dx, int rows, int H, int kind, hipStream_t s);
+hipError_t attn_delta_vec(const void *o, long ldo, const void *dout, long lddo, float *delta, int B, int Sq, int A, int d,
+                          hipStream_t s);
 hipError_t colreduce1_vec(const void *a, long lda, const void *x, const float *mean, const float *rstd, int kind,
                           float *partial, int rows, int cols, int chunks, bool norm, hipStream_t s);
 

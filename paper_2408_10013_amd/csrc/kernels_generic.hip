@@ -547,6 +547,10 @@ hipError_t attn_bwd(const Attn &a, hipStream_t s) {
 
 hipError_t attn_delta(const Attn &a, hipStream_t s) {
   AttnP p = to_p(a);
+  if (a.dtype == SSDT_BF16) {
+    hipError_t e = attn_delta_vec(a.o, a.ldo, a.dout, a.lddo, a.delta, a.B, a.Sq, a.A, a.d, s);
+    if (e != hipErrorNotSupported) return e;
+  }
   dim3 gq((a.Sq + 3) / 4, a.A, a.B);
   if (a.dtype == SSDT_F32) hipLaunchKernelGGL(attn_delta_k<float>, gq, dim3(256), 0, s, p);
   else hipLaunchKernelGGL(attn_delta_k<bf16>, gq, dim3(256), 0, s, p);

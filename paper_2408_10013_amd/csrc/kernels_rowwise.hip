@@ -211,6 +211,31 @@ __global__ __launch_bounds__(256) void colreduce1_vec_k(const uint16_t *a, long 
   }
 }
 
+// delta[b, h, i] = sum_c o[b, i, h, c] dout[b, i, h, c] for bf16 rows that hold the heads side by side (head size a
+// power of two between 8 and 512): one wavefront per token walks the row of o and of dout with 16-byte loads
+// (d/8 lanes per head), multiplies, and adds the lanes of a head together.
+__global__ __launch_bounds__(256) void attn_delta_vec_k(const uint16_t *o, long ldo, const uint16_t *dO, long lddo, float *delta,
+                                                        long rows, int Sq, int A, int d) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const long row = (long)blockIdx.x * 4 + w;  // b * Sq + i
+  if (row >= rows) return;
+  const int b = (int)(row / Sq), i = (int)(row % Sq), H = A * d, lph = d >> 3;
+  o += row * ldo;
+  dO += row * lddo;
+  for (int c = lane * 8; c < H; c += 512) {
+    const u32x4_nt a = __builtin_nontemporal_load((const u32x4_nt *)(o + c));
+    const uint4 g = *(const uint4 *)(dO + c);  // read again by the backward kernels that follow
+    float x[8], y[8];
+    unpack8(make_uint4(a.x, a.y, a.z, a.w), x);
+    unpack8(g, y);
+    float s = 0.f;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) s = fmaf(x[t], y[t], s);
+    for (int m = 1; m < lph; m <<= 1) s += __shfl_xor(s, m, 64);
+    if ((lane & (lph - 1)) == 0) delta[((long)b * A + c / d) * Sq + i] = s;
+  }
+}
+
 static int pick_nch(int H) {
   const int need = (H / 8 + 63) / 64;
   for (int n : {1, 2, 4, 8, 16})
@@ -242,6 +267,16 @@ hipError_t norm_bwd_dx_vec(const void *dy, const void *x, const float *mean, con
                                       (const uint16_t *)gamma, (const uint16_t *)resid, (uint16_t *)dx, rows, H, kind)
   switch (nch) { case 1: SSDT_GO(1); break; case 2: SSDT_GO(2); break; case 4: SSDT_GO(4); break; case 8: SSDT_GO(8); break; default: SSDT_GO(16); }
 #undef SSDT_GO
+  return hipGetLastError();
+}
+
+hipError_t attn_delta_vec(const void *o, long ldo, const void *dout, long lddo, float *delta, int B, int Sq, int A, int d,
+                          hipStream_t s) {
+  const int lph = d / 8;
+  if (d % 8 || lph < 1 || lph > 64 || (lph & (lph - 1)) || ldo % 8 || lddo % 8 || !al16(o) || !al16(dout)) return hipErrorNotSupported;
+  const long rows = (long)B * Sq;
+  hipLaunchKernelGGL(attn_delta_vec_k, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, (const uint16_t *)o, ldo,
+                     (const uint16_t *)dout, lddo, delta, rows, Sq, A, d);
   return hipGetLastError();
 }
 
