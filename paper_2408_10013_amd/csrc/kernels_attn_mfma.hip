@@ -36,7 +36,6 @@ struct FaP {
 };
 
 constexpr float kLog2e = 1.4426950408889634f;
-constexpr float kLn2 = 0.6931471805599453f;
 
 // 8 bf16 for an MFMA operand taken from a k-major LDS tile T[k][i] (row stride ld elements):
 // lane (i = lane % 32) receives T[k_lo + 0..3][i0 + i] and T[k_hi + 0..3][i0 + i].
@@ -378,7 +377,7 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dkv_k(FaP p) {
     }
     if (p.mask == SSDT_MASK_CAUSAL && i0 + BQ - 1 < k0) continue;  // every query of the tile precedes this wavefront's keys
     const bool need_mask = (p.mask == SSDT_MASK_CAUSAL && i0 < k0 + 31) || (k0 + 32 > limit);
-#pragma unroll(LEAN ? 1 : 2)
+#pragma unroll LEAN ? 1 : 2
     for (int qb = 0; qb < 2; ++qb) {
       f32x16_t sacc, dpacc;
 #pragma unroll
