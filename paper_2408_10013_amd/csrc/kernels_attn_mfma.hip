@@ -221,16 +221,6 @@ __global__ __launch_bounds__(256, 2) void fa_fwd_k(FaP p) {
     const float mnew = fmaxf(m, mloc);
     const bool move = __builtin_amdgcn_ballot_w64((mnew - m) * sc > kLazy) != 0;  // uniform over the wavefront
     const float mref = move ? mnew : m, moff = (mref == -INFINITY) ? 0.f : -mref * sc;
-    float lsum = 0.f;
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float e = __builtin_amdgcn_exp2f(fmaf(sacc[kb][r], sc, moff));
-        sacc[kb][r] = e;
-        lsum += e;
-      }
-    lsum += __shfl_xor(lsum, 32, 64);
     if (move) {
       const float corr = __builtin_amdgcn_exp2f(fmaf(m, sc, moff));
       l *= corr;
@@ -240,20 +230,27 @@ __global__ __launch_bounds__(256, 2) void fa_fwd_k(FaP p) {
         for (int r = 0; r < 16; ++r) oacc[d][r] *= corr;
       m = mnew;
     }
-    l += lsum;
-    // O^T += V^T P^T, 16 keys per step
+    // O^T += V^T P^T, 16 keys per step; the exponentials of a step's eight scores sit next to its MFMAs, so that the
+    // exponentials of the following step can be issued while those MFMAs run
+    float lsum = 0.f;
 #pragma unroll
     for (int s4 = 0; s4 < 4; ++s4) {
       const int kb = s4 >> 1, g = (s4 & 1) * 2;
-      float pa[4] = {sacc[kb][g * 4 + 0], sacc[kb][g * 4 + 1], sacc[kb][g * 4 + 2], sacc[kb][g * 4 + 3]};
-      float pb[4] = {sacc[kb][g * 4 + 4], sacc[kb][g * 4 + 5], sacc[kb][g * 4 + 6], sacc[kb][g * 4 + 7]};
-      bf16x8_t pf = pack8(pa, pb);
+      float pe[8];
+#pragma unroll
+      for (int r = 0; r < 8; ++r) {
+        pe[r] = __builtin_amdgcn_exp2f(fmaf(sacc[kb][g * 4 + r], sc, moff));
+        lsum += pe[r];
+      }
+      bf16x8_t pf = pack8(pe, pe + 4);
 #pragma unroll
       for (int d = 0; d < DB; ++d) {
         bf16x8_t vf = frag_tr(sV, LV, s4 * 16 + half * 4, s4 * 16 + 8 + half * 4, d * 32, lane);
         oacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, oacc[d], 0, 0, 0);
       }
     }
+    lsum += __shfl_xor(lsum, 32, 64);
+    l += lsum;
   }
   const float inv = l > 0.f ? 1.f / l : 0.f;
   uint16_t *op = p.out + (long)(b * p.Sq + qi) * p.ldo + h * D;
