@@ -567,31 +567,36 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dkv128_k(FaP p) {
     if (w == 0) __builtin_amdgcn_global_load_lds(stat_g + tile * BQ, (lds_void_t *)dst, 4, 0, 0);
   };
 
+  // Query tiles are taken from the last one down to tile tstart: the key blocks of a head, which run side by side on
+  // one XCD, then all start on the same tile and walk the same Q / dO rows at the same time, so that one block's L2
+  // misses are the others' hits (in ascending order every block starts at its own diagonal and the kernel fetched
+  // three times its operands through the L2).  step s works on query tile rev(s).
+  auto rev = [&](int s) { return nt - 1 + tstart - s; };
   if (tstart < nt) {
     dma_tile128<128>(p.v + (long)(b * p.Sk + kblock) * p.ldv + h * D, (int)p.ldv, sV, w, lane);
-    dma_tile128<BQ>(qg + (long)tstart * BQ * p.ldq, (int)p.ldq, sQ0, w, lane);
-    dma_tile128<BQ>(dog + (long)tstart * BQ * p.lddo, (int)p.lddo, sdO0, w, lane);
-    dma_stat(tstart, sStat0);
+    dma_tile128<BQ>(qg + (long)rev(tstart) * BQ * p.ldq, (int)p.ldq, sQ0, w, lane);
+    dma_tile128<BQ>(dog + (long)rev(tstart) * BQ * p.lddo, (int)p.lddo, sdO0, w, lane);
+    dma_stat(rev(tstart), sStat0);
   }
-  // tile t sits in buffer (t - tstart) & 1; while it is consumed, tile t+1 loads into the other buffer
+  // step s's tile sits in buffer (s - tstart) & 1; while it is consumed, the next step's tile loads into the other buffer
   for (int t = tstart; t < nt; t += 2) {
-    __builtin_amdgcn_s_waitcnt(0xF70);  // vmcnt(0): this wavefront's loads of tile t have landed
+    __builtin_amdgcn_s_waitcnt(0xF70);  // vmcnt(0): this wavefront's loads of the tile have landed
     __syncthreads();                    // everyone's have, and everyone is done with the other buffer
     if (t + 1 < nt) {
-      dma_tile128<BQ>(qg + (long)(t + 1) * BQ * p.ldq, (int)p.ldq, sQ1, w, lane);
-      dma_tile128<BQ>(dog + (long)(t + 1) * BQ * p.lddo, (int)p.lddo, sdO1, w, lane);
-      dma_stat(t + 1, sStat1);
+      dma_tile128<BQ>(qg + (long)rev(t + 1) * BQ * p.ldq, (int)p.ldq, sQ1, w, lane);
+      dma_tile128<BQ>(dog + (long)rev(t + 1) * BQ * p.lddo, (int)p.lddo, sdO1, w, lane);
+      dma_stat(rev(t + 1), sStat1);
     }
-    dkv128_tile(p, sQ0, sdO0, sV, sStat0, sStat0 + BQ, kf, dkacc, dvacc, t * BQ, k0, limit, w, lane);
+    dkv128_tile(p, sQ0, sdO0, sV, sStat0, sStat0 + BQ, kf, dkacc, dvacc, rev(t) * BQ, k0, limit, w, lane);
     if (t + 1 >= nt) break;
     __builtin_amdgcn_s_waitcnt(0xF70);
     __syncthreads();
     if (t + 2 < nt) {
-      dma_tile128<BQ>(qg + (long)(t + 2) * BQ * p.ldq, (int)p.ldq, sQ0, w, lane);
-      dma_tile128<BQ>(dog + (long)(t + 2) * BQ * p.lddo, (int)p.lddo, sdO0, w, lane);
-      dma_stat(t + 2, sStat0);
+      dma_tile128<BQ>(qg + (long)rev(t + 2) * BQ * p.ldq, (int)p.ldq, sQ0, w, lane);
+      dma_tile128<BQ>(dog + (long)rev(t + 2) * BQ * p.lddo, (int)p.lddo, sdO0, w, lane);
+      dma_stat(rev(t + 2), sStat0);
     }
-    dkv128_tile(p, sQ1, sdO1, sV, sStat1, sStat1 + BQ, kf, dkacc, dvacc, (t + 1) * BQ, k0, limit, w, lane);
+    dkv128_tile(p, sQ1, sdO1, sV, sStat1, sStat1 + BQ, kf, dkacc, dvacc, rev(t + 1) * BQ, k0, limit, w, lane);
   }
   uint16_t *dkp = p.dk + (long)(b * p.Sk + kj) * p.lddk + h * D, *dvp = p.dv + (long)(b * p.Sk + kj) * p.lddv + h * D;
 #pragma unroll
