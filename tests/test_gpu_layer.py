@@ -145,6 +145,9 @@ VARIANTS = {
     # and three 64-wide stages: its prologue and its peeled last stages without the steady-state loop between
     "gpt_thin128": dict(arch="gpt_preln", B=2, S=2048, H=128, A=2, F=4096, act="gelu", norm="layernorm", mask="causal", has_bias=True, eps=1e-5),
     "gpt_thin192": dict(arch="gpt_preln", B=2, S=2048, H=192, A=3, F=4096, act="gelu", norm="layernorm", mask="causal", has_bias=True, eps=1e-5),
+    # eight heads of size 128 over five query / key blocks: the attention kernels' re-ordered block indices (heads dealt
+    # to the XCDs, an odd number of blocks per head) and the key-side backward's descending walk over 20 query tiles
+    "gpt_heads8": dict(arch="gpt_preln", B=4, S=640, H=256, A=2, F=512, act="gelu", norm="layernorm", mask="causal", has_bias=True, eps=1e-5),
 }
 
 
