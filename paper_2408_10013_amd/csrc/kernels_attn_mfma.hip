@@ -82,9 +82,19 @@ __device__ __forceinline__ void load_tile(const uint16_t *g, long ld, int valid,
 
 // the same copy split in two, so that the global loads of the next tile can be in flight while the
 // current tile is consumed: tile_gload issues the loads into registers, tile_sstore writes them to LDS
-template <int D, int ROWS>
+// (FAST: a whole tile, the usual case, is loaded without per-row predicates and zero fill; worth 3-5 % in the forward
+// kernel, while the key-side backward at head size 64 lost 15 % with it, so it is opt-in)
+template <int D, int ROWS, bool FAST = false>
 __device__ __forceinline__ void tile_gload(const uint16_t *g, long ld, int valid, int tid, uint4 (&r)[ROWS * (D / 8) / 256]) {
   constexpr int CPR = D / 8, N = ROWS * CPR / 256;
+  if (FAST && valid >= ROWS) {
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      int c = tid + i * 256, row = c / CPR, kc = c % CPR;
+      r[i] = *(const uint4 *)(g + (long)row * ld + kc * 8);
+    }
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < N; ++i) {
     int c = tid + i * 256, row = c / CPR, kc = c % CPR;
@@ -167,8 +177,8 @@ __global__ __launch_bounds__(256, 2) void fa_fwd_k(FaP p) {
 
   uint4 rk[BKV * (D / 8) / 256], rv[BKV * (D / 8) / 256];
   if (ntiles > 0) {
-    tile_gload<D, BKV>(kg, p.ldk, p.Sk, tid, rk);
-    tile_gload<D, BKV>(vg, p.ldv, p.Sk, tid, rv);
+    tile_gload<D, BKV, true>(kg, p.ldk, p.Sk, tid, rk);
+    tile_gload<D, BKV, true>(vg, p.ldv, p.Sk, tid, rv);
   }
   for (int t = 0; t < ntiles; ++t) {
     const int j0 = t * BKV;
@@ -177,8 +187,8 @@ __global__ __launch_bounds__(256, 2) void fa_fwd_k(FaP p) {
     tile_sstore<D, BKV, LV>(sV, tid, rv);
     __syncthreads();
     if (t + 1 < ntiles) {  // next tile's loads fly under this tile's MFMAs
-      tile_gload<D, BKV>(kg + (long)(j0 + BKV) * p.ldk, p.ldk, p.Sk - j0 - BKV, tid, rk);
-      tile_gload<D, BKV>(vg + (long)(j0 + BKV) * p.ldv, p.ldv, p.Sk - j0 - BKV, tid, rv);
+      tile_gload<D, BKV, true>(kg + (long)(j0 + BKV) * p.ldk, p.ldk, p.Sk - j0 - BKV, tid, rk);
+      tile_gload<D, BKV, true>(vg + (long)(j0 + BKV) * p.ldv, p.ldv, p.Sk - j0 - BKV, tid, rv);
     }
     if (p.mask == SSDT_MASK_CAUSAL && j0 > q0 + 31) continue;  // tile entirely above this wavefront's diagonal
     f32x16_t sacc[2];
