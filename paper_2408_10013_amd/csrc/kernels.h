@@ -86,7 +86,7 @@ struct Attn {
   long lddo = 0;
   void *dq = nullptr, *dk = nullptr, *dv = nullptr;
   long lddq = 0, lddk = 0, lddv = 0;
-  float *delta = nullptr;  // scratch [B, A, Sq]
+  float *delta = nullptr;  // scratch, 2 x [B, A, Sq] floats (the second half holds lse in base-2 units for the matrix-core backward)
 };
 hipError_t attn_fwd(const Attn &a, hipStream_t s);
 hipError_t attn_bwd(const Attn &a, hipStream_t s);

@@ -408,10 +408,8 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dkv_k(FaP p) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int r = g * 4 + e;
-          float pe = __builtin_amdgcn_exp2f(sacc[r] * sc - lv[e] * kLog2e);
-          bool dead = lv[e] == -INFINITY;
-          if (need_mask) dead = dead || kj >= limit || (p.mask == SSDT_MASK_CAUSAL && kj > i0 + qo + e);
-          pe = dead ? 0.f : pe;
+          float pe = __builtin_amdgcn_exp2f(fmaf(sacc[r], sc, -lv[e]));  // lv: lse in base-2 units, +inf for a row without keys
+          if (need_mask && (kj >= limit || (p.mask == SSDT_MASK_CAUSAL && kj > i0 + qo + e))) pe = 0.f;
           pv[r] = pe;
           dsv[r] = pe * (dpacc[r] - dv[e]);
         }
@@ -512,10 +510,8 @@ __device__ __forceinline__ void dkv128_tile(const FaP &p, const uint16_t *sQ, co
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       const int r = g * 4 + e;
-      float pe = __builtin_amdgcn_exp2f(sacc[r] * sc - lv[e] * kLog2e);
-      bool dead = lv[e] == -INFINITY;
-      if (need_mask) dead = dead || kj >= limit || (p.mask == SSDT_MASK_CAUSAL && kj > i0 + qo + e);
-      pe = dead ? 0.f : pe;
+      float pe = __builtin_amdgcn_exp2f(fmaf(sacc[r], sc, -lv[e]));  // lv: lse in base-2 units, +inf for a row without keys
+      if (need_mask && (kj >= limit || (p.mask == SSDT_MASK_CAUSAL && kj > i0 + qo + e))) pe = 0.f;
       pv[r] = pe;
       dsv[r] = pe * (dpacc[r] - dv[e]);
     }
@@ -648,8 +644,7 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dq_k(FaP p) {
   }
   const long si = ((long)b * p.A + h) * p.Sq + qi;
   const float lse = p.lse[si], delta = p.delta[si];
-  const bool row_dead = lse == -INFINITY;
-  const float lse2 = row_dead ? 0.f : lse * kLog2e;
+  const float lse2 = lse;  // base-2 units, +inf for a row without keys (see attn_bwd_mfma_bf16)
   int limit = p.Sk;
   if (p.mask == SSDT_MASK_CAUSAL) limit = min(limit, qb * 128 + 128);
   if (p.mask == SSDT_MASK_KEYPAD) limit = min(limit, max(0, p.kv_len[b]));
@@ -703,13 +698,11 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dq_k(FaP p) {
       float dsv[16];
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        float pe = __builtin_amdgcn_exp2f(sacc[r] * sc - lse2);
-        bool dead = row_dead;
+        float pe = __builtin_amdgcn_exp2f(fmaf(sacc[r], sc, -lse2));
         if (need_mask) {
           const int key = j0 + kb * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
-          dead = dead || key >= limit || (p.mask == SSDT_MASK_CAUSAL && key > qi);
+          if (key >= limit || (p.mask == SSDT_MASK_CAUSAL && key > qi)) pe = 0.f;
         }
-        pe = dead ? 0.f : pe;
         dsv[r] = pe * (dpacc[r] - delta);
       }
 #pragma unroll
@@ -743,6 +736,11 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dq_k(FaP p) {
                      pack_bf2(dqacc[d][g * 4 + 2] * p.scale, dqacc[d][g * 4 + 3] * p.scale));
 }
 
+__global__ void lse_base2_k(const float *lse, float *out, long n) {
+  const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) out[i] = lse[i] == -INFINITY ? INFINITY : lse[i] * kLog2e;
+}
+
 int g_attn_kb = 0;  // test hook: 1 pins the register-staged key-side kernel
 
 hipError_t attn_bwd_mfma_bf16(const Attn &a, hipStream_t s) {
@@ -757,6 +755,12 @@ hipError_t attn_bwd_mfma_bf16(const Attn &a, hipStream_t s) {
   hipError_t e = attn_delta(a, s);
   if (e != hipSuccess) return e;
   FaP p = to_fa(a);
+  // the kernels recompute P = exp2(s scale log2(e) - lse2) with lse2 = lse log2(e), and +inf for a query without
+  // any admissible key (P = 0 without a test per element); lse2 sits behind delta in the caller's scratch
+  const long nstat = (long)a.B * a.A * a.Sq;
+  float *lse2 = a.delta + nstat;
+  hipLaunchKernelGGL(lse_base2_k, dim3((unsigned)((nstat + 255) / 256)), dim3(256), 0, s, a.lse, lse2, nstat);
+  p.lse = lse2;
   dim3 gk(a.Sk / 128, a.A, a.B), gq(a.Sq / 128, a.A, a.B);
   if (a.d == 128) {
     const bool dma = (((uintptr_t)a.q | (uintptr_t)a.v | (uintptr_t)a.dout) & 15) == 0 && a.ldq % 8 == 0 && a.ldv % 8 == 0 &&

@@ -86,7 +86,7 @@ void bwd_layout(const Dims &D, Ws &w, BwdBufs *b) {
   size_t rows = std::max(D.T, D.Te), cols = max3(3 * (size_t)D.H, D.F, 0);
   b->partial = (float *)w.take(k::colreduce_partial_floats((int)rows, (int)cols) * 4);
   b->partial_side = (float *)w.take(k::colreduce_partial_floats((int)rows, (int)cols) * 4);
-  b->delta = (float *)w.take((size_t)D.B * D.A * D.S * 4);
+  b->delta = (float *)w.take((size_t)2 * D.B * D.A * D.S * 4);  // delta, and lse in base-2 units behind it
   b->scratch_bytes = bwd_scratch(D);
   b->scratch = b->scratch_bytes ? w.take(b->scratch_bytes) : nullptr;
 }
