@@ -331,6 +331,25 @@ typedef struct ssdt_layer_saved {
  * below need for `desc`.  E_INVAL / E_UNSUPPORTED for an unusable description. */
 ssdt_status ssdt_layer_workspace(const ssdt_layer_desc *desc, size_t *fwd_bytes, size_t *bwd_bytes);
 
+/* Where ssdt_layer_bwd leaves its intermediate gradients: byte offsets from `ws` (for inspection and for
+ * tests that check one operator of the backward at a time; nothing else needs them).  The contents are those of
+ * the last ssdt_layer_bwd with this description, once its work on the stream has finished, and stay until the
+ * next call that is given the workspace.  All are [B*S, width] in desc.dtype.
+ *   d_h1  [T,F]   gradient w.r.t. the FC1 output (pre-activation)
+ *   d_qkv [T,3H]  gradient w.r.t. the fused Q|K|V projection
+ *   t0, t1, t2 [T,H]: for the pre-norm variants without cross-attention (GPT_PRELN, T5_ENC) t1 = gradient
+ *         w.r.t. x1 (the residual stream between the two blocks), t0 = gradient w.r.t. the attention output o,
+ *         t2 = gradient w.r.t. the first norm's output a (it held the gradient w.r.t. the second norm's output
+ *         m earlier in the call).  BERT_POSTLN: t0 = gradient w.r.t. r2 then w.r.t. o, t1 = gradient w.r.t. x1
+ *         then w.r.t. the attention block's input branch, t2 = gradient w.r.t. r1.  T5_DEC reuses them once more
+ *         for the cross-attention block.
+ *   d_kvx [T_enc,2H] T5_DEC only (else 0): gradient w.r.t. the fused K|V projection of the encoder output
+ * E_INVAL / E_UNSUPPORTED as for ssdt_layer_workspace. */
+typedef struct ssdt_bwd_temporaries {
+  uint64_t d_h1, t0, t1, t2, d_qkv, d_kvx;
+} ssdt_bwd_temporaries;
+ssdt_status ssdt_layer_bwd_temporaries(const ssdt_layer_desc *desc, ssdt_bwd_temporaries *out);
+
 /* Forward of one layer, enqueued on `stream`, as scope `scope` of the current step.
  *   x        DEVICE [B*S, H]: an arena block (ssdt_arena_alloc, or the previous layer's *y) whose
  *            ownership passes to the registry, or caller memory (then it is never freed here)

@@ -87,6 +87,10 @@ class ssdt_layer_desc(C.Structure):
                                                         ("checkpoint", C.c_int32), ("accumulate", C.c_int32)]
 
 
+class ssdt_bwd_temporaries(C.Structure):
+    _fields_ = [(n, C.c_uint64) for n in ("d_h1", "t0", "t1", "t2", "d_qkv", "d_kvx")]
+
+
 class ssdt_layer_weights(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in WEIGHT_NAMES]
 
@@ -132,6 +136,7 @@ _PROTOS = {
     "ssdt_profile_read": (C.c_int32, [C.c_void_p, C.POINTER(ssdt_kernel_time), C.c_uint32, C.POINTER(C.c_uint32)]),
     "ssdt_sgd_update": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_int32, C.c_float, C.c_void_p]),
     "ssdt_layer_workspace": (C.c_int32, [C.POINTER(ssdt_layer_desc), C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]),
+    "ssdt_layer_bwd_temporaries": (C.c_int32, [C.POINTER(ssdt_layer_desc), C.POINTER(ssdt_bwd_temporaries)]),
     "ssdt_layer_fwd": (C.c_int32, [C.c_void_p, C.POINTER(ssdt_layer_desc), C.POINTER(ssdt_layer_weights), C.c_int32,
                                    C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_void_p),
                                    C.POINTER(ssdt_layer_saved), C.c_void_p, C.c_size_t, C.c_void_p]),
@@ -333,6 +338,12 @@ def ssdt_layer_workspace(desc: ssdt_layer_desc):
     f, b = C.c_size_t(), C.c_size_t()
     _check(None, lib().ssdt_layer_workspace(C.byref(desc), C.byref(f), C.byref(b)), "ssdt_layer_workspace")
     return f.value, b.value
+
+
+def ssdt_layer_bwd_temporaries(desc: ssdt_layer_desc) -> dict:
+    out = ssdt_bwd_temporaries()
+    _check(None, lib().ssdt_layer_bwd_temporaries(C.byref(desc), C.byref(out)), "ssdt_layer_bwd_temporaries")
+    return {n: int(getattr(out, n)) for n, _ in out._fields_}
 
 
 def ssdt_layer_fwd(ctx, desc, weights, scope, x, enc_out, kv_len, ws, ws_bytes, stream=0):

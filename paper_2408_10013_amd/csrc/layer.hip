@@ -113,6 +113,22 @@ ssdt_status ssdt_layer_workspace(const ssdt_layer_desc *desc, size_t *fwd_bytes,
   return SSDT_OK;
 }
 
+ssdt_status ssdt_layer_bwd_temporaries(const ssdt_layer_desc *desc, ssdt_bwd_temporaries *out) {
+  Dims D;
+  std::string why;
+  ssdt_status s = check_desc(desc, &D, &why);
+  if (s != SSDT_OK) return s;
+  if (!out) return SSDT_E_INVAL;
+  char *base = (char *)(uintptr_t)4096;  // any 256-byte aligned non-null address: only differences are reported
+  Ws w(base, ~(size_t)0 >> 1);
+  BwdBufs b;
+  bwd_layout(D, w, &b);
+  auto off = [&](void *p) { return p ? (uint64_t)((char *)p - base) : 0; };
+  out->d_h1 = off(b.dh1); out->t0 = off(b.t0); out->t1 = off(b.t1); out->t2 = off(b.t2);
+  out->d_qkv = off(b.dqkv); out->d_kvx = off(b.dkvx);
+  return SSDT_OK;
+}
+
 ssdt_status ssdt_layer_fwd(ssdt_ctx *ctx, const ssdt_layer_desc *desc, const ssdt_layer_weights *w, int32_t scope,
                            const void *x, const void *enc_out, const int32_t *kv_len, void **y_out,
                            ssdt_layer_saved *saved, void *ws, size_t ws_bytes, ssdt_stream stream) {

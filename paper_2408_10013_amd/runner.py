@@ -107,6 +107,9 @@ class Stack:
         # input, backward re-runs the layer's forward inside its backward scope
         self.recompute = False
         self.mb_saved: Dict[int, list] = {}
+        # set to a dict to keep copies of every layer's output ("y"), activation output ("g") and input gradient
+        # ("dx") of the next forward / backward pass, and the accumulated encoder-output gradient ("d_enc")
+        self.capture: Optional[dict] = None
 
     def close(self):
         if self.ctx:
@@ -156,6 +159,11 @@ class Stack:
                 l = self.layers[i]
                 y, l.saved = sb.ssdt_layer_fwd(ctx, l.desc_ckpt if self.recompute else l.desc, l.wstruct, i, p, enc, kvp,
                                                self.ws_ptr, self.ws_bytes, self.stream)
+                if self.capture is not None:
+                    self.capture.setdefault("y", {})[i] = self.view(y, (l.T, l.H)).clone()
+                    ge = l.saved.e[sb.SV_NAMES.index("g")]
+                    if l.act == "relu" and ge.ptr and ge.bytes:
+                        self.capture.setdefault("g", {})[i] = self.view(ge.ptr, (l.T, l.F)).clone()
                 if offload:
                     sb.ssdt_offload(ctx, i, self.stream)
                 sb.ssdt_arena_free(ctx, p, self.stream)   # drop the caller's reference on the layer input
@@ -216,10 +224,14 @@ class Stack:
                 if self.recompute:
                     sb.ssdt_scope_end(ctx, i, sb.BWD)
                 sb.ssdt_release(ctx, i, self.stream)
+                if self.capture is not None:
+                    self.capture.setdefault("dx", {})[i] = out.clone()
                 cur, flip = out, flip ^ 1
             return cur
 
         dx = run(L, n_enc, dy, d_enc.data_ptr() if d_enc is not None else 0)
+        if self.capture is not None and d_enc is not None:
+            self.capture["d_enc"] = d_enc
         if n_enc:
             dx_enc = run(n_enc, 0, d_enc, 0)
             return dx, dx_enc
