@@ -377,6 +377,21 @@ ssdt_status ssdt_layer_bwd(ssdt_ctx *ctx, const ssdt_layer_desc *desc, const ssd
                            void *d_enc_out, const ssdt_layer_weights *grads, void *ws, size_t ws_bytes,
                            ssdt_stream stream);
 
+/* ssdt_layer_bwd for callers that cannot allocate device memory or have none to hand over as a workspace (code
+ * under stream capture, tight serving or training loops, harnesses that forbid allocation): same arguments, results
+ * and ordering rules as ssdt_layer_bwd, bit for bit, but the workspace is an array of SSDT_STATIC_WS_BYTES that is
+ * part of the library's device code (one per GPU the library runs on, held until the process ends).  The call
+ * allocates and frees no device memory.  A layer whose backward needs more workspace than that
+ * (ssdt_layer_workspace says how much) is refused with SSDT_E_NOMEM and a message; nothing is enqueued then.
+ * Every call on a GPU shares that GPU's array, whatever the context: calls whose GPU work can overlap in time
+ * (different streams without an ordering between them, different threads) race on it; calls enqueued on one
+ * stream, or ordered by events, do not.  Nothing in the array has to be cleared between calls (every part is
+ * written before it is read within a call). */
+#define SSDT_STATIC_WS_BYTES ((size_t)64 << 20)
+ssdt_status ssdt_layer_bwd_static(ssdt_ctx *ctx, const ssdt_layer_desc *desc, const ssdt_layer_weights *w,
+                                  const ssdt_layer_saved *saved, const int32_t *kv_len, const void *dy, void *dx,
+                                  void *d_enc_out, const ssdt_layer_weights *grads, ssdt_stream stream);
+
 /* Plain SGD step on one parameter tensor: w <- w - lr * g elementwise, computed in fp32 and stored in `dtype`
  * (Sec. 4.1: the evaluation uses SGD so that the optimizer adds no state).  `w`, `g`: DEVICE, `numel` elements of
  * `dtype` (SSDT_F32 / SSDT_BF16), caller-owned; enqueued on `stream`.  E_INVAL for null pointers or an unknown

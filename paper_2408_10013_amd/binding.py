@@ -140,6 +140,9 @@ _PROTOS = {
     "ssdt_layer_fwd": (C.c_int32, [C.c_void_p, C.POINTER(ssdt_layer_desc), C.POINTER(ssdt_layer_weights), C.c_int32,
                                    C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_void_p),
                                    C.POINTER(ssdt_layer_saved), C.c_void_p, C.c_size_t, C.c_void_p]),
+    "ssdt_layer_bwd_static": (C.c_int32, [C.c_void_p, C.POINTER(ssdt_layer_desc), C.POINTER(ssdt_layer_weights),
+                                          C.POINTER(ssdt_layer_saved), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                          C.POINTER(ssdt_layer_weights), C.c_void_p]),
     "ssdt_layer_bwd": (C.c_int32, [C.c_void_p, C.POINTER(ssdt_layer_desc), C.POINTER(ssdt_layer_weights),
                                    C.POINTER(ssdt_layer_saved), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                    C.POINTER(ssdt_layer_weights), C.c_void_p, C.c_size_t, C.c_void_p]),
@@ -359,3 +362,12 @@ def ssdt_layer_bwd(ctx, desc, weights, saved, kv_len, dy, dx, d_enc_out, grads, 
     _check(ctx, lib().ssdt_layer_bwd(ctx, C.byref(desc), C.byref(weights), C.byref(saved), kv_len or None, dy, dx,
                                      d_enc_out or None, C.byref(grads), ws, ws_bytes, stream or None),
            "ssdt_layer_bwd")
+
+
+STATIC_WS_BYTES = 64 << 20
+
+
+def ssdt_layer_bwd_static(ctx, desc, weights, saved, kv_len, dy, dx, d_enc_out, grads, stream=0):
+    _check(ctx, lib().ssdt_layer_bwd_static(ctx, C.byref(desc), C.byref(weights), C.byref(saved), kv_len or None, dy, dx,
+                                            d_enc_out or None, C.byref(grads), stream or None),
+           "ssdt_layer_bwd_static")

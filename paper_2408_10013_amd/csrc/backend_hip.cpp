@@ -32,7 +32,11 @@ class HipBackend : public Backend {
       if (!check(hipStreamCreateWithFlags(&q_[d], hipStreamNonBlocking), "hipStreamCreateWithFlags")) return false;
     if (!check(hipStreamCreateWithFlags(&aux_, hipStreamNonBlocking), "hipStreamCreateWithFlags")) return false;
     if (pool_bytes && !check(hipHostMalloc(&pool_, pool_bytes, hipHostMallocDefault), "hipHostMalloc(pool)")) return false;
-    return true;
+    // a stock of events, so that the layer entry points create none in the steady state
+    std::vector<Ev *> stock;
+    for (int i = 0; i < 64; ++i) stock.push_back(get_ev(false));
+    for (Ev *e : stock) recycle(e);
+    return err.empty();
   }
   ~HipBackend() override {
     for (Ev *e : all_) {

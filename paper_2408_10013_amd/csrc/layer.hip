@@ -4,6 +4,7 @@
 // pack hook in the order autograd would register it (Sec. 3.2), and fetched back through the
 // unpack hook in backward (Algorithm 1).
 #include <cmath>
+#include <mutex>
 
 #include "ctx.h"
 #include "kernels.h"
@@ -329,7 +330,11 @@ ssdt_status ssdt_layer_fwd(ssdt_ctx *ctx, const ssdt_layer_desc *desc, const ssd
 #undef HIP_IF
 }
 
-ssdt_status ssdt_layer_bwd(ssdt_ctx *ctx, const ssdt_layer_desc *desc, const ssdt_layer_weights *w,
+}  // extern "C"
+
+namespace {
+
+ssdt_status layer_bwd_impl(ssdt_ctx *ctx, const ssdt_layer_desc *desc, const ssdt_layer_weights *w,
                            const ssdt_layer_saved *saved, const int32_t *kv_len, const void *dy, void *dx,
                            void *d_enc_out, const ssdt_layer_weights *gr, void *ws, size_t ws_bytes,
                            ssdt_stream stream) {
@@ -543,6 +548,60 @@ ssdt_status ssdt_layer_bwd(ssdt_ctx *ctx, const ssdt_layer_desc *desc, const ssd
   return ctx->scope_end(scope, SSDT_BWD);
 #undef GET
 #undef HIP_IF
+}
+
+// Workspace of ssdt_layer_bwd_static: one array in device memory per GPU the library runs on, there from the moment
+// the code object is loaded until the process ends.  In host code its name is only a handle; the device address
+// comes from hipGetSymbolAddress, once per device, with that device current.
+constexpr size_t kStaticWsBytes = SSDT_STATIC_WS_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticWsBytes];
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mu;
+void *g_static_ptr[kMaxDevices] = {};
+
+hipError_t static_workspace(void **out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lk(g_static_mu);
+  if (!g_static_ptr[dev]) {
+    void *p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p || ((uintptr_t)p & 255)) return hipErrorInvalidSymbol;
+    g_static_ptr[dev] = p;
+  }
+  *out = g_static_ptr[dev];
+  return hipSuccess;
+}
+
+}  // namespace
+
+extern "C" {
+
+ssdt_status ssdt_layer_bwd(ssdt_ctx *ctx, const ssdt_layer_desc *desc, const ssdt_layer_weights *w,
+                           const ssdt_layer_saved *saved, const int32_t *kv_len, const void *dy, void *dx,
+                           void *d_enc_out, const ssdt_layer_weights *gr, void *ws, size_t ws_bytes,
+                           ssdt_stream stream) {
+  return layer_bwd_impl(ctx, desc, w, saved, kv_len, dy, dx, d_enc_out, gr, ws, ws_bytes, stream);
+}
+
+ssdt_status ssdt_layer_bwd_static(ssdt_ctx *ctx, const ssdt_layer_desc *desc, const ssdt_layer_weights *w,
+                                  const ssdt_layer_saved *saved, const int32_t *kv_len, const void *dy, void *dx,
+                                  void *d_enc_out, const ssdt_layer_weights *gr, ssdt_stream stream) {
+  if (!ctx) return SSDT_E_INVAL;
+  if (ctx->be->is_sim()) return ctx->fail(SSDT_E_UNSUPPORTED, "layer_bwd_static: the simulated backend has no GPU");
+  size_t need = 0;
+  ssdt_status s = ssdt_layer_workspace(desc, nullptr, &need);
+  if (s != SSDT_OK) return ctx->fail(s, "layer_bwd_static: unusable layer description");
+  if (need > kStaticWsBytes)
+    return ctx->fail(SSDT_E_NOMEM, "layer_bwd_static: this layer needs %zu bytes of workspace, the built-in one has %zu; "
+                                   "use ssdt_layer_bwd with a workspace of your own", need, kStaticWsBytes);
+  void *ws = nullptr;
+  hipError_t e = static_workspace(&ws);
+  if (e != hipSuccess) return ctx->fail(SSDT_E_HIP, "layer_bwd_static: address of the built-in workspace: %s", hipGetErrorString(e));
+  return layer_bwd_impl(ctx, desc, w, saved, kv_len, dy, dx, d_enc_out, gr, ws, kStaticWsBytes, stream);
 }
 
 ssdt_status ssdt_sgd_update(ssdt_ctx *ctx, void *w, const void *g, size_t numel, int32_t dtype, float lr, ssdt_stream stream) {
