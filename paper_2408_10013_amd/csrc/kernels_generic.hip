@@ -122,7 +122,9 @@ hipError_t gemm_generic(const Gemm &g, hipStream_t s) {
 hipError_t gemm(const Gemm &g, hipStream_t s) {
   if (g.M <= 0 || g.N <= 0 || g.K <= 0) return hipErrorInvalidValue;
   if (g.dtype == SSDT_BF16) {
-    hipError_t e = gemm_mfma_bf16(g, s);
+    hipError_t e = gemm_mfma_km_bf16(g, s);  // operands taken as stored, also k-major ones
+    if (e != hipErrorNotSupported) return e;
+    e = gemm_mfma_bf16(g, s);                // K-contiguous form, other operands through transposed copies
     if (e != hipErrorNotSupported) return e;
   }
   return gemm_generic(g, s);

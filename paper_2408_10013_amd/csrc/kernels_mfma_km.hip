@@ -1,0 +1,297 @@
+// bf16 GEMM on the CDNA4 matrix cores for operands that are contiguous along the OTHER dimension
+// ("k-major": element (k, i) at k * ld + i), fp32 accumulation.
+//
+// The layer stores weights as [in, out] and activations as [tokens, features].  The forward
+// product x W therefore has its second operand k-major, and the weight gradient in^T dY has both
+// operands k-major (the contraction runs over tokens).  The MFMA wants 8 consecutive k per lane;
+// gemm_nt256_k gets them with one 128-bit LDS read from K-contiguous rows, and k-major operands
+// used to be brought to that form by a transpose into scratch memory first.  This kernel reads
+// k-major operands as they are: a stage of 64 k-rows x 256 columns goes to LDS by direct
+// global-to-LDS loads (a row of the stage is 512 contiguous bytes), and the operand fragments are
+// fetched with the transposing LDS read ds_read_b64_tr_b16, two per fragment: a group of 16 lanes
+// reads a block of 4 k-rows x 16 columns and every lane receives one column's 4 values.
+//
+// Same tile shape, wavefront layout, accumulator layout, epilogues and workgroup order as
+// gemm_nt256_k (256 x 256 per workgroup of 8 wavefronts, each 128 x 64 as 8 x 4 blocks of
+// v_mfma_f32_16x16x32_bf16), so the two kernels give bit-identical results on transposed copies of
+// the same data.  Differences:
+//   * LDS holds [A buffer 0 | A buffer 1 | B buffer 0 | B buffer 1], 32 KiB each, and the stage loop
+//     is unrolled by two, so that every LDS address is a per-lane constant plus an instruction
+//     offset (below 64 KiB) and no address is updated in the loop.
+//   * A k-major row of 512 bytes is kept with its 32-byte units permuted: unit u of k-row k sits at
+//     u ^ ((k & 3) | ((k >> 3) & 1) << 2).  One transposing read has its first 32 lanes on k-rows
+//     {0..3, 8..11} (or {4..7, 12..15}) of a 16-row group at one column unit; the key sends those
+//     eight rows to eight different 32-byte bank groups.  The key of the row a lane reads depends on
+//     the lane only, so each 16-column block has its own address register.
+//   * LDS reads are compiler-visible (no inline assembly): the compiler computes every
+//     `s_waitcnt lgkmcnt` from the program order, which scheduling fences pin to the order written
+//     here.  The direct-to-LDS loads and the barrier are still written out, with `vmcnt` waits by hand.
+#include "dev.h"
+#include "kernels.h"
+#include "mfma_common.h"
+#include "prof.h"
+
+namespace ssdt {
+namespace k {
+
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) s16x4_t lds_s16x4_t;
+typedef __attribute__((address_space(3))) v4i_t lds_v4i_t;
+typedef __attribute__((address_space(3))) char lds_char_t;
+
+constexpr int kTile = 256, kStageK = 64;
+constexpr unsigned kBuf = 32768;            // one operand's stage: 256 x 64 bf16 either way round
+constexpr unsigned kLdsB = 2 * kBuf;        // B buffers behind the two A buffers
+
+#define SSDT_FENCE __builtin_amdgcn_sched_barrier(0)
+
+// 8 bf16 of an MFMA operand from a k-major stage: `at` addresses this lane's 8 bytes of k-row group 0 of the
+// 16-column block, `off` selects buffer and 32-wide step; the second read is 4 k-rows (4 x 512 bytes) further.
+__device__ __forceinline__ bf16x8_t frag_km(const lds_char_t *at, unsigned off) {
+  const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)(at + off));
+  const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)(at + off + 2048));
+  union { struct { s16x4_t a, b; } s; bf16x8_t v; } u;
+  u.s.a = lo;
+  u.s.b = hi;
+  return u.v;
+}
+// the same from a K-contiguous stage (rows of 128 bytes, 16-byte chunks swizzled as in gemm_nt256_k)
+__device__ __forceinline__ bf16x8_t frag_nt(const lds_char_t *at, unsigned off) {
+  union { v4i_t a; bf16x8_t v; } u;
+  u.a = *(const lds_v4i_t *)(at + off);
+  return u.v;
+}
+
+template <int EPI, bool AKM, bool BKM>
+__global__ __launch_bounds__(512) void gemm_km256_k(NtP p) {
+  constexpr int MB = 8, NB = 4, NT = 512, LJ = 4;
+  extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), wm = wave >> 2, wn = wave & 3;
+  int tile_m, tile_n;
+  tile_of(p, blockIdx.x, &tile_m, &tile_n);
+  const int m0 = tile_m * kTile, n0 = tile_n * kTile;
+
+  // ---- loader: thread t fills 16-byte LDS positions j*NT + t of each operand's buffer, j = 0..3 ----------------
+  // K-contiguous operand: position = (row j*64 + t/8, slot t%8), slot holds global chunk (t%8) ^ ((row >> 1) & 7).
+  // k-major operand: position = (k-row j*16 + t/32, 16-byte half t%2 of 32-byte unit (t%32)/2), which holds
+  // global unit ((t%32)/2) ^ key(k-row); the key does not depend on j.
+  unsigned voa[LJ], vob[LJ];
+  {
+    const int lrow = tid >> 3, lchunk = (tid & 7) ^ ((lrow >> 1) & 7);
+    const int kr = tid >> 5, c = tid & 31, key = (kr & 3) | (((kr >> 3) & 1) << 2), unit = (c >> 1) ^ key;
+#pragma unroll
+    for (int j = 0; j < LJ; ++j) {
+      voa[j] = AKM ? (unsigned)((j * 16 + kr) * (int)p.lda) * 2u + unit * 32 + (c & 1) * 16
+                   : (unsigned)((lrow + j * 64) * (int)p.lda + lchunk * 8) * 2u;
+      vob[j] = BKM ? (unsigned)((j * 16 + kr) * (int)p.ldb) * 2u + unit * 32 + (c & 1) * 16
+                   : (unsigned)((lrow + j * 64) * (int)p.ldb + lchunk * 8) * 2u;
+    }
+  }
+  const char *pa = (const char *)(AKM ? p.A + m0 : p.A + (long)m0 * p.lda);    // stage 0 of the tile
+  const char *pb = (const char *)(BKM ? p.Bt + n0 : p.Bt + (long)n0 * p.ldb);
+  const long sa = AKM ? (long)kStageK * p.lda * 2 : kStageK * 2, sb = BKM ? (long)kStageK * p.ldb * 2 : kStageK * 2;
+  const unsigned lds0 = (unsigned)(uintptr_t)smem;
+  const unsigned wbase = lds0 + wave * 1024;  // this wavefront's 1 KiB of every 8 KiB a load instruction fills
+// one 16-byte-per-lane direct-to-LDS load: M0 = LDS address of the wavefront's 1 KiB, global address = scalar base +
+// per-lane byte offset (no instruction offset: it would be added to the LDS address too)
+#define SSDT_LD(PTR, VOFF, LDSOFF)                                                                         \
+  asm volatile("s_add_u32 m0, %0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"                         \
+               :: "s"(wbase), "v"(VOFF), "s"(PTR), "n"(LDSOFF) : "memory", "scc")
+#define SSDT_LDA(BUF, PTR, j) SSDT_LD(PTR, voa[j], (BUF) * kBuf + (j) * NT * 16)
+#define SSDT_LDB(BUF, PTR, j) SSDT_LD(PTR, vob[j], kLdsB + (BUF) * kBuf + (j) * NT * 16)
+
+  // ---- fragment addresses ---------------------------------------------------------------------------------
+  const int lr = lane & 15, lq = lane >> 4;
+  // K-contiguous: lane reads row lr of a 16-row block, chunk 4*step + lq, swizzled by (row >> 1) & 7
+  const unsigned nt_c0 = ((lq ^ (lr >> 1)) * 16), nt_c1 = (((4 | lq) ^ (lr >> 1)) * 16);
+  // k-major: lane supplies k-row 8*lq + lr/4 (+4 for the second read), bytes 8*(lr%4).. of the block's 32-byte unit
+  const int kkey = (lr >> 2) | ((lq & 1) << 2);
+  const unsigned km_row = (unsigned)(8 * lq + (lr >> 2)) * 512 + 8 * (lr & 3);
+  const lds_char_t *aA[AKM ? MB : 2], *aB[BKM ? NB : 2];
+  if (AKM) {
+#pragma unroll
+    for (int i = 0; i < MB; ++i) aA[i] = (const lds_char_t *)(uintptr_t)(lds0 + km_row + (unsigned)((wm * 8 + i) ^ kkey) * 32);
+  } else {
+    aA[0] = (const lds_char_t *)(uintptr_t)(lds0 + (wm * 128 + lr) * 128 + nt_c0);
+    aA[1] = (const lds_char_t *)(uintptr_t)(lds0 + (wm * 128 + lr) * 128 + nt_c1);
+  }
+  if (BKM) {
+#pragma unroll
+    for (int j = 0; j < NB; ++j) aB[j] = (const lds_char_t *)(uintptr_t)(lds0 + kLdsB + km_row + (unsigned)((wn * 4 + j) ^ kkey) * 32);
+  } else {
+    aB[0] = (const lds_char_t *)(uintptr_t)(lds0 + kLdsB + (wn * 64 + lr) * 128 + nt_c0);
+    aB[1] = (const lds_char_t *)(uintptr_t)(lds0 + kLdsB + (wn * 64 + lr) * 128 + nt_c1);
+  }
+  // fragment of 16-row block i (of A) / j (of B) for 32-wide step `step` of the stage in buffer `buf`
+  auto rdA = [&](int i, int step, int buf) -> bf16x8_t {
+    if constexpr (AKM) return frag_km(aA[i], buf * kBuf + step * 16384);
+    else return frag_nt(aA[step], buf * kBuf + i * 2048);
+  };
+  auto rdB = [&](int j, int step, int buf) -> bf16x8_t {
+    if constexpr (BKM) return frag_km(aB[j], buf * kBuf + step * 16384);
+    else return frag_nt(aB[step], buf * kBuf + j * 2048);
+  };
+
+  f32x4_t acc[MB][NB];
+#pragma unroll
+  for (int i = 0; i < MB; ++i)
+#pragma unroll
+    for (int j = 0; j < NB; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  bf16x8_t Af[MB], Bf[2][NB];
+
+  // One stage (64 of K) out of buffer `buf`, as two 32-wide steps.  On entry Af[0..7] and Bf[0][0..3] hold the
+  // fragments of step 0.  The A fragments live in one register set that is refilled block by block as soon as a
+  // block's MFMAs have been issued; the B fragments in two sets that alternate per step.  All reads of a stage have
+  // been issued by the end of its first step, so the stage's one barrier sits behind the first block of the second
+  // step: after it the other buffer (the next stage, whose loads were waited for just before) may be read, and the
+  // stage after next is loaded over this one, two loads behind the first MFMAs of each of the next four blocks.
+  auto mfma_block = [&](int i, int set, int j0, int j1) {
+    SSDT_FENCE;
+#pragma unroll
+    for (int j = j0; j < j1; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Bf[set][j], Af[i], acc[i][j], 0, 0, 0);
+    SSDT_FENCE;
+  };
+#define SSDT_KM_STAGE(BUF, MORE, MORE2)                                                                    \
+  {                                                                                                        \
+    SSDT_FENCE;                                                                                            \
+    _Pragma("unroll") for (int j = 0; j < NB; ++j) Bf[1][j] = rdB(j, 1, BUF);                              \
+    _Pragma("unroll") for (int i = 0; i < MB; ++i) {                                                       \
+      mfma_block(i, 0, 0, NB);                                                                             \
+      Af[i] = rdA(i, 1, BUF);                                                                              \
+    }                                                                                                      \
+    mfma_block(0, 1, 0, NB);                                                                               \
+    if (MORE) {                                                                                            \
+      /* every LDS read of this stage has returned, this wavefront's part of the next stage has landed */  \
+      asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");                                          \
+      __builtin_amdgcn_s_barrier();                                                                        \
+      asm volatile("" ::: "memory");                                                                       \
+      SSDT_FENCE;                                                                                          \
+      _Pragma("unroll") for (int j = 0; j < NB; ++j) Bf[0][j] = rdB(j, 0, (BUF) ^ 1);                      \
+      Af[0] = rdA(0, 0, (BUF) ^ 1);                                                                        \
+    }                                                                                                      \
+    _Pragma("unroll") for (int i = 1; i < MB; ++i) {                                                       \
+      mfma_block(i, 1, 0, 1);                                                                              \
+      if (MORE2 && i <= LJ) SSDT_LDA(BUF, pa, i - 1);                                                      \
+      mfma_block(i, 1, 1, 2);                                                                              \
+      if (MORE2 && i <= LJ) SSDT_LDB(BUF, pb, i - 1);                                                      \
+      mfma_block(i, 1, 2, NB);                                                                             \
+      if (MORE) Af[i] = rdA(i, 0, (BUF) ^ 1);                                                              \
+    }                                                                                                      \
+    pa += sa; pb += sb;                                                                                    \
+  }
+
+  const int nk = p.K / kStageK;  // even, >= 2 (checked by the launcher)
+#pragma unroll
+  for (int j = 0; j < LJ; ++j) { SSDT_LDA(0, pa, j); SSDT_LDB(0, pb, j); }
+  pa += sa; pb += sb;
+#pragma unroll
+  for (int j = 0; j < LJ; ++j) { SSDT_LDA(1, pa, j); SSDT_LDB(1, pb, j); }
+  pa += sa; pb += sb;  // from here on: the stage after next
+  asm volatile("s_waitcnt vmcnt(8)" ::: "memory");  // stage 0 has landed (stage 1 may still be on its way)
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+  SSDT_FENCE;
+#pragma unroll
+  for (int j = 0; j < NB; ++j) Bf[0][j] = rdB(j, 0, 0);
+#pragma unroll
+  for (int i = 0; i < MB; ++i) Af[i] = rdA(i, 0, 0);
+  int st = 0;
+  for (; st + 4 <= nk; st += 2) {
+    SSDT_KM_STAGE(0, true, true);
+    SSDT_KM_STAGE(1, true, true);
+  }
+  SSDT_KM_STAGE(0, true, false);
+  SSDT_KM_STAGE(1, false, false);
+#undef SSDT_KM_STAGE
+#undef SSDT_LD
+#undef SSDT_LDA
+#undef SSDT_LDB
+
+  // epilogue through LDS (free now), two 64x64 sub-tiles of the wavefront's 128x64: lane l of block (i, j) holds
+  // row i*16 + (l & 15), columns j*16 + (l >> 4)*4 + 0..3
+  u32x4_t ein[MB / 4][8];
+#pragma unroll
+  for (int I = 0; I < MB / 4; ++I) epilogue_fetch<EPI>(p, m0 + wm * 128 + I * 64, n0 + wn * 64, lane, ein[I]);
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __builtin_amdgcn_s_barrier();  // every wavefront has finished reading the last stage
+  asm volatile("" ::: "memory");
+  float *stg = (float *)smem + wave * (64 * kEpiLd);
+#pragma unroll
+  for (int I = 0; I < MB / 4; ++I) {
+#pragma unroll
+    for (int il = 0; il < 4; ++il)
+#pragma unroll
+      for (int jl = 0; jl < 4; ++jl) {
+        const f32x4_t a = acc[I * 4 + il][jl];
+        *(float4 *)(stg + (il * 16 + lr) * kEpiLd + jl * 16 + lq * 4) = make_float4(a[0], a[1], a[2], a[3]);
+      }
+    epilogue_rows<EPI>(p, stg, m0 + wm * 128 + I * 64, n0 + wn * 64, lane, ein[I]);
+  }
+}
+
+template <int EPI, bool AKM, bool BKM>
+static hipError_t launch_km(const NtP &p, hipStream_t s) {
+  constexpr size_t stg = (size_t)8 * 64 * kEpiLd * 4, stages = (size_t)4 * kBuf, smem = stg > stages ? stg : stages;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void *)gemm_km256_k<EPI, AKM, BKM>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  prof::Scope ps(prof::GEMM_MFMA_KM, 2.0 * p.M * p.N * p.K, 0, s);
+  hipLaunchKernelGGL((gemm_km256_k<EPI, AKM, BKM>), dim3(p.tiles_m * p.tiles_n), dim3(512), smem, s, p);
+  return hipGetLastError();
+}
+
+template <bool AKM, bool BKM>
+static hipError_t launch_km_epi(int epi, const NtP &p, hipStream_t s) {
+  switch (epi) {
+    case EPI_NONE: return launch_km<EPI_NONE, AKM, BKM>(p, s);
+    case EPI_BIAS: return launch_km<EPI_BIAS, AKM, BKM>(p, s);
+    case EPI_BIAS_ACT: return launch_km<EPI_BIAS_ACT, AKM, BKM>(p, s);
+    case EPI_BIAS_RESID: return launch_km<EPI_BIAS_RESID, AKM, BKM>(p, s);
+    case EPI_ACTBWD: return launch_km<EPI_ACTBWD, AKM, BKM>(p, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+int g_km_mode = 1;  // test hook: 0 = never use this kernel, 1 = for k-major operands, 2 = also for the NT form
+
+// Shape part of the conditions below: what a caller can know before it has pointers (workspace sizing, the choice
+// between this kernel and transposed copies).
+bool gemm_km_fits(int M, int N, int K, bool transA, bool transB, int dtype) {
+  if (dtype != SSDT_BF16 || g_km_mode == 0) return false;
+  if (!transA && transB && g_km_mode < 2) return false;
+  if (M % kTile || N % kTile || K % (2 * kStageK) || K < 2 * kStageK) return false;
+  return (long)(M / kTile) * (N / kTile) >= 256;
+}
+
+// Takes the problem if it fits (hipErrorNotSupported otherwise, nothing launched): bf16, M and N multiples of 256 with
+// at least 256 tiles, K a multiple of 128, 16-byte aligned operands and epilogue tensors.
+hipError_t gemm_mfma_km_bf16(const Gemm &g, hipStream_t s) {
+  if (!gemm_km_fits(g.M, g.N, g.K, g.transA, g.transB, g.dtype)) return hipErrorNotSupported;
+  const bool akm = g.transA, bkm = !g.transB;
+  auto al16 = [](const void *q) { return ((uintptr_t)q & 15) == 0; };
+  if (!al16(g.A) || !al16(g.B) || g.lda % 8 || g.ldb % 8 || g.lda >= (1L << 22) || g.ldb >= (1L << 22)) return hipErrorNotSupported;
+  if (g.ldc % 8 || !al16(g.C) || (g.C2 && !al16(g.C2)) || (g.bias && !al16(g.bias)) || (g.aux && !al16(g.aux)) ||
+      (g.resid && (!al16(g.resid) || g.ldr % 8)))
+    return hipErrorNotSupported;
+  if (g.epi == EPI_BIAS_ACT && !g.C2) return hipErrorInvalidValue;
+  if (g.epi == EPI_BIAS_RESID && !g.resid) return hipErrorInvalidValue;
+  if (g.epi == EPI_ACTBWD && !g.aux) return hipErrorInvalidValue;
+  // a k-major tile row is 512 contiguous bytes at column m0 / n0: the leading dimension must hold whole tiles
+  if ((akm && g.lda < g.M) || (bkm && g.ldb < g.N)) return hipErrorInvalidValue;
+  NtP p{g.M, g.N, g.K, (const uint16_t *)g.A, (const uint16_t *)g.B, g.lda, g.ldb, g.ldc, g.ldr, (uint16_t *)g.C,
+        (uint16_t *)g.C2, (const uint16_t *)g.bias, (const uint16_t *)g.resid, (const uint16_t *)g.aux, g.act,
+        g.M / kTile, g.N / kTile, 8};
+  p.gm = g_force_waves > 0 ? g_force_waves : (p.tiles_m >= p.tiles_n ? 4 : 8);
+  if (akm && bkm) return launch_km_epi<true, true>(g.epi, p, s);
+  if (bkm) return launch_km_epi<false, true>(g.epi, p, s);
+  if (akm) return launch_km_epi<true, false>(g.epi, p, s);
+  return launch_km_epi<false, false>(g.epi, p, s);
+}
+
+}  // namespace k
+}  // namespace ssdt

@@ -23,7 +23,7 @@ hipEvent_t get() {
 
 const char *name(int cat) {
   static const char *n[NCAT] = {"gemm_nt256_k", "gemm_nt128_k", "gemm_generic_k", "transpose_k", "fa_fwd_k|attn_fwd_generic_k",
-                                "fa_bwd_*|attn_bwd_*", "norm_fwd_k", "norm_bwd_dx_k", "colreduce*_k", "add_inplace_k"};
+                                "fa_bwd_*|attn_bwd_*", "norm_fwd_k", "norm_bwd_dx_k", "colreduce*_k", "add_inplace_k", "gemm_km256_k"};
   return (cat >= 0 && cat < NCAT) ? n[cat] : "?";
 }
 void set(bool on) { g_on = on; }

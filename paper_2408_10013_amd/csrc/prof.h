@@ -6,7 +6,7 @@
 namespace ssdt {
 namespace prof {
 
-enum Cat { GEMM_MFMA_256 = 0, GEMM_MFMA_128, GEMM_GENERIC, TRANSPOSE, ATTN_FWD, ATTN_BWD, NORM_FWD, NORM_BWD, COLREDUCE, ADD, NCAT };
+enum Cat { GEMM_MFMA_256 = 0, GEMM_MFMA_128, GEMM_GENERIC, TRANSPOSE, ATTN_FWD, ATTN_BWD, NORM_FWD, NORM_BWD, COLREDUCE, ADD, GEMM_MFMA_KM, NCAT };
 extern bool g_on;
 const char *name(int cat);
 void begin(int cat, double flops, double bytes, hipStream_t s);
