@@ -54,6 +54,7 @@ extern int g_force_tile;                                // 0 = choose; 128 / 256
 // rows raised the kernel's L2 miss rate from 20 % to 34 %; neutral on the other shapes).
 inline long nt_copy_ld(int K) { return ((long)K * 2) % 32768 == 0 ? (long)K + 64 : (long)K; }
 size_t gemm_scratch_bytes(int M, int N, int K, bool transA, bool transB, int dtype);
+size_t gemm_nt_scratch_bytes(int M, int N, int K, bool transA, bool transB, int dtype);  // gemm_mfma_bf16's own need
 
 // Row norm over H.  kind = SSDT_NORM_*.  mean may be null for RMSNorm.
 hipError_t norm_fwd(const void *x, const void *gamma, const void *beta, void *y, float *mean, float *rstd, int rows,

@@ -357,13 +357,18 @@ static inline size_t up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 static inline bool al16(const void *p) { return ((uintptr_t)p & 15) == 0; }
 static inline bool al8(const void *p) { return ((uintptr_t)p & 7) == 0; }
 
-size_t gemm_scratch_bytes(int M, int N, int K, bool transA, bool transB, int dtype) {
+// what gemm_mfma_bf16 itself needs: room for a K-contiguous copy of every operand that is not stored that way
+size_t gemm_nt_scratch_bytes(int M, int N, int K, bool transA, bool transB, int dtype) {
   if (dtype != SSDT_BF16) return 0;
-  if (gemm_km_fits(M, N, K, transA, transB, dtype)) return 0;  // operands are read as stored
   size_t b = 0;
   if (transA) b += up((size_t)M * nt_copy_ld(K) * 2, 256);
   if (!transB) b += up((size_t)N * nt_copy_ld(K) * 2, 256);
   return b;
+}
+// what gemm() can make use of: nothing where the kernel that reads operands as stored takes the problem
+size_t gemm_scratch_bytes(int M, int N, int K, bool transA, bool transB, int dtype) {
+  if (gemm_km_fits(M, N, K, transA, transB, dtype)) return 0;
+  return gemm_nt_scratch_bytes(M, N, K, transA, transB, dtype);
 }
 
 
@@ -376,7 +381,7 @@ hipError_t gemm_mfma_bf16(const Gemm &g, hipStream_t s) {
   if (g.epi == EPI_BIAS_ACT && !g.C2) return hipErrorInvalidValue;
   if (g.epi == EPI_BIAS_RESID && !g.resid) return hipErrorInvalidValue;
   if (g.epi == EPI_ACTBWD && !g.aux) return hipErrorInvalidValue;
-  size_t need = gemm_scratch_bytes(g.M, g.N, g.K, g.transA, g.transB, g.dtype);
+  size_t need = gemm_nt_scratch_bytes(g.M, g.N, g.K, g.transA, g.transB, g.dtype);
   if (need && (!g.scratch || g.scratch_bytes < need || !al16(g.scratch))) return hipErrorNotSupported;
   const uint16_t *A = (const uint16_t *)g.A, *Bt = (const uint16_t *)g.B;
   long lda = g.lda, ldb = g.ldb;

@@ -141,22 +141,24 @@ __global__ __launch_bounds__(512) void gemm_km256_k(NtP p) {
     for (int j = 0; j < NB; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
   bf16x8_t Af[MB], Bf[2][NB];
 
-  // One stage (64 of K) out of buffer `buf`, as two 32-wide steps.  On entry Af[0..7] and Bf[0][0..3] hold the
-  // fragments of step 0.  The A fragments live in one register set that is refilled block by block as soon as a
-  // block's MFMAs have been issued; the B fragments in two sets that alternate per step.  All reads of a stage have
-  // been issued by the end of its first step, so the stage's one barrier sits behind the first block of the second
-  // step: after it the other buffer (the next stage, whose loads were waited for just before) may be read, and the
-  // stage after next is loaded over this one, two loads behind the first MFMAs of each of the next four blocks.
+  // One stage (64 of K) is two 32-wide steps.  The A fragments live in one register set that is refilled block by
+  // block as soon as a block's MFMAs have been issued; the B fragments in two sets that alternate per step.  All reads
+  // of a stage have been issued by the end of its first step, so the stage's one barrier sits behind the first block
+  // of the second step: after it the other buffer (the next stage, whose loads were waited for just before) may be
+  // read, and the stage after next is loaded over this one, two loads behind the first MFMAs of each of the next four
+  // blocks.  The code is written as the two halves either side of that barrier, and the loop is cut there, where no
+  // LDS read is outstanding (with the cut at the stage boundary the compiler, which does not carry its count of
+  // outstanding reads around a loop, waited for all of them at the head of every iteration).
   auto mfma_block = [&](int i, int set, int j0, int j1) {
     SSDT_FENCE;
 #pragma unroll
     for (int j = j0; j < j1; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Bf[set][j], Af[i], acc[i][j], 0, 0, 0);
     SSDT_FENCE;
   };
-#define SSDT_KM_STAGE(BUF, MORE, MORE2)                                                                    \
+// first half of the stage in buffer BUF: step 0 and the first block of step 1, then the barrier.  On entry Af[0..7]
+// and Bf[0][0..3] hold the fragments of step 0 and the reads of Bf[1][0..3] (step 1) have been issued.
+#define SSDT_KM_HEAD(BUF, MORE)                                                                            \
   {                                                                                                        \
-    SSDT_FENCE;                                                                                            \
-    _Pragma("unroll") for (int j = 0; j < NB; ++j) Bf[1][j] = rdB(j, 1, BUF);                              \
     _Pragma("unroll") for (int i = 0; i < MB; ++i) {                                                       \
       mfma_block(i, 0, 0, NB);                                                                             \
       Af[i] = rdA(i, 1, BUF);                                                                              \
@@ -168,6 +170,13 @@ __global__ __launch_bounds__(512) void gemm_km256_k(NtP p) {
       __builtin_amdgcn_s_barrier();                                                                        \
       asm volatile("" ::: "memory");                                                                       \
       SSDT_FENCE;                                                                                          \
+    }                                                                                                      \
+  }
+// second half: the rest of step 1 out of the registers, while the next stage (buffer BUF ^ 1) is read and the stage
+// after next is loaded into buffer BUF.  MORE / MORE2: a next stage / a stage after next exists.
+#define SSDT_KM_TAIL(BUF, MORE, MORE2)                                                                     \
+  {                                                                                                        \
+    if (MORE) {                                                                                            \
       _Pragma("unroll") for (int j = 0; j < NB; ++j) Bf[0][j] = rdB(j, 0, (BUF) ^ 1);                      \
       Af[0] = rdA(0, 0, (BUF) ^ 1);                                                                        \
     }                                                                                                      \
@@ -178,6 +187,11 @@ __global__ __launch_bounds__(512) void gemm_km256_k(NtP p) {
       if (MORE2 && i <= LJ) SSDT_LDB(BUF, pb, i - 1);                                                      \
       mfma_block(i, 1, 2, NB);                                                                             \
       if (MORE) Af[i] = rdA(i, 0, (BUF) ^ 1);                                                              \
+    }                                                                                                      \
+    if (MORE) {                                                                                            \
+      SSDT_FENCE;                                                                                          \
+      _Pragma("unroll") for (int j = 0; j < NB; ++j) Bf[1][j] = rdB(j, 1, (BUF) ^ 1);                      \
+      SSDT_FENCE;                                                                                          \
     }                                                                                                      \
     pa += sa; pb += sb;                                                                                    \
   }
@@ -197,14 +211,21 @@ __global__ __launch_bounds__(512) void gemm_km256_k(NtP p) {
   for (int j = 0; j < NB; ++j) Bf[0][j] = rdB(j, 0, 0);
 #pragma unroll
   for (int i = 0; i < MB; ++i) Af[i] = rdA(i, 0, 0);
-  int st = 0;
-  for (; st + 4 <= nk; st += 2) {
-    SSDT_KM_STAGE(0, true, true);
-    SSDT_KM_STAGE(1, true, true);
+#pragma unroll
+  for (int j = 0; j < NB; ++j) Bf[1][j] = rdB(j, 1, 0);
+  SSDT_FENCE;
+  SSDT_KM_HEAD(0, true);
+  for (int st = 0; st + 4 <= nk; st += 2) {
+    SSDT_KM_TAIL(0, true, true);
+    SSDT_KM_HEAD(1, true);
+    SSDT_KM_TAIL(1, true, true);
+    SSDT_KM_HEAD(0, true);
   }
-  SSDT_KM_STAGE(0, true, false);
-  SSDT_KM_STAGE(1, false, false);
-#undef SSDT_KM_STAGE
+  SSDT_KM_TAIL(0, true, false);
+  SSDT_KM_HEAD(1, false);
+  SSDT_KM_TAIL(1, false, false);
+#undef SSDT_KM_HEAD
+#undef SSDT_KM_TAIL
 #undef SSDT_LD
 #undef SSDT_LDA
 #undef SSDT_LDB
