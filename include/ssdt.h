@@ -81,9 +81,12 @@ typedef struct ssdt_config {
   size_t pool_bytes;          /* pinned host pool, allocated once at create (Sec. 3.1, CPU offloader) */
   const char *spill_path;     /* HOST string or NULL.  If set (Sec. 3.1, SSD offloader): the file is created
                                  or truncated at create (SSDT_E_IO if that fails) and becomes the store,
-                                 the pool its staging buffer.  A worker thread writes every offloaded
+                                 the pool its staging buffer.  The file is opened for direct I/O (O_DIRECT:
+                                 pinned pool to device without the page cache) where the file system allows it,
+                                 and every tensor then starts on a 4096-byte boundary of pool and file instead
+                                 of a 256-byte one.  Worker threads write every offloaded
                                  tensor to the file, at its pool offset, once its copy out of the device
-                                 has completed, and then overwrites the tensor's pool bytes; a prefetch
+                                 has completed, and then overwrite the tensor's pool bytes; a prefetch
                                  reads the tensor back into the pool, and the copy into the device is
                                  enqueued by the first later call on the context that finds the read
                                  complete (ssdt_get blocks the host for it if need be).  A failed
@@ -91,7 +94,8 @@ typedef struct ssdt_config {
                                  ssdt_sync_io / ssdt_step_begin return SSDT_E_IO. */
   int32_t measure_waits;      /* nonzero: bracket every wait of a compute stream on a load with timing
                                  events so that ssdt_get_stats can report exposed I/O time */
-  int32_t reserved;
+  int32_t spill_threads;      /* threads serving the spill file (each with one request of up to 8 MiB at the
+                                 device at a time); 0 = 4 */
 } ssdt_config;
 
 typedef struct ssdt_stats {
@@ -102,8 +106,9 @@ typedef struct ssdt_stats {
   uint64_t loads, bytes_loaded, forwarded, demand_loads, released;
   /* arena */
   uint64_t arena_in_use, arena_high_water, arena_peak_in_use, arena_allocs;
-  /* time (ns) compute streams spent blocked on loads / on arena slots still being stored; valid
-     after the streams have been synchronised, 0 unless measure_waits */
+  /* time (ns) compute streams spent blocked on loads / on arena slots still being stored during the current
+     step (cleared by ssdt_step_begin like the other counters); complete once the streams have been
+     synchronised, 0 unless measure_waits */
   uint64_t exposed_load_wait_ns, exposed_store_wait_ns;
 } ssdt_stats;
 
@@ -215,8 +220,8 @@ ssdt_status ssdt_scope_end(ssdt_ctx *ctx, int32_t scope, int32_t phase);
  * reused, also not when a later storage has the same address) and later saves of any view of it are
  * dedup hits; the current scope is added to its scope list; at the first save it is classed KEPT
  * (layer among the last keep_last, or offloaded-so-far + bytes > budget, or the host pool is full)
- * or OFFLOADED and given its place in the layer's pack (256-byte aligned, first-save order; packs
- * are rounded to 4096 bytes and follow each other in the pool).  `*out` = stamp, or 0 if bypassed.
+ * or OFFLOADED and given its place in the layer's pack (256-byte aligned, 4096 with a spill file; first-save
+ * order; packs are rounded to 4096 bytes and follow each other in the pool).  `*out` = stamp, or 0 if bypassed.
  * E_STATE outside a forward scope. */
 ssdt_status ssdt_save(ssdt_ctx *ctx, const void *storage_base, size_t storage_bytes, size_t view_offset,
                       const int64_t *shape, int32_t ndim, int32_t dtype, ssdt_tid *out);
@@ -257,6 +262,14 @@ ssdt_status ssdt_sync_io(ssdt_ctx *ctx);
 /* Bytes written to and read from the spill file since create (either pointer may be NULL, HOST).
  * SSDT_E_STATE if the context has no spill file. */
 ssdt_status ssdt_spill_stats(ssdt_ctx *ctx, uint64_t *bytes_written, uint64_t *bytes_read);
+/* The same with the rest of what the file tier can report (HOST struct, filled): whether direct I/O is in
+ * effect, the number of threads, and the wall time during which at least one write (read) request was at the
+ * device, so that bytes / busy time is the file's write (read) rate as the offload path drives it. */
+typedef struct ssdt_spill_info_t {
+  int32_t direct_io, threads;
+  uint64_t bytes_written, bytes_read, write_busy_ns, read_busy_ns;
+} ssdt_spill_info_t;
+ssdt_status ssdt_spill_info(ssdt_ctx *ctx, ssdt_spill_info_t *out);
 
 /* ---- kernel timing ------------------------------------------------------------------------ */
 

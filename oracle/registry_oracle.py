@@ -32,8 +32,9 @@ micro-batches.
 
 Host-pool layout: the OFFLOADED storages of one layer (the scope at the bottom of the
 scope stack) form a pack, in first-save order, each starting at the next multiple of
-256 bytes; a pack's size is rounded up to 4096 bytes; packs follow each other in the
-order their layers first appear.
+256 bytes (of 4096 bytes when the pool is backed by a spill file, whose direct I/O works in
+whole blocks: `tensor_align`); a pack's size is rounded up to 4096 bytes; packs follow each
+other in the order their layers first appear.
 """
 from __future__ import annotations
 
@@ -80,7 +81,8 @@ class Counters:
 class RegistryOracle:
     def __init__(self, num_layers: int, min_offload_elems: int = 1 << 20,
                  budget_bytes: Optional[int] = None, keep_last: int = 1,
-                 pool_bytes: Optional[int] = None):
+                 pool_bytes: Optional[int] = None, tensor_align: int = ALIGN_TENSOR):
+        self.tensor_align = tensor_align
         self.num_layers = num_layers
         self.min_elems = min_offload_elems
         self.budget = budget_bytes
@@ -160,7 +162,7 @@ class RegistryOracle:
             return 0
         in_last = layer[1] >= self.num_layers - self.mb_keep_last.get(layer[0], self.keep_last)
         over = self.budget is not None and c.bytes_offloaded + storage_bytes > self.budget
-        off = _up(self.pack_cursor[layer], ALIGN_TENSOR)
+        off = _up(self.pack_cursor[layer], self.tensor_align)
         nomem = (self.pool_bytes is not None and
                  _up(self.pack_base[layer] + off + storage_bytes, ALIGN_PACK) > self.pool_bytes)
         if in_last or over or nomem or self.in_backward > 0:

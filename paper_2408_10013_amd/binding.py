@@ -43,7 +43,7 @@ class ssdt_config(C.Structure):
     _fields_ = [("backend", C.c_int32), ("keep_last", C.c_int32), ("min_offload_elems", C.c_int64),
                 ("budget_bytes", C.c_int64), ("arena_base", C.c_void_p), ("arena_bytes", C.c_size_t),
                 ("pool_bytes", C.c_size_t), ("spill_path", C.c_char_p), ("measure_waits", C.c_int32),
-                ("reserved", C.c_int32)]
+                ("spill_threads", C.c_int32)]
 
 
 class ssdt_stats(C.Structure):
@@ -63,6 +63,11 @@ class ssdt_record(C.Structure):
                 ("n_scopes", C.c_int32), ("bytes", C.c_uint64), ("pack_offset", C.c_int64),
                 ("pool_offset", C.c_int64), ("device_ptr", C.c_void_p), ("micro_batch", C.c_int32),
                 ("reserved", C.c_int32)]
+
+
+class ssdt_spill_info_t(C.Structure):
+    _fields_ = [("direct_io", C.c_int32), ("threads", C.c_int32), ("bytes_written", C.c_uint64),
+                ("bytes_read", C.c_uint64), ("write_busy_ns", C.c_uint64), ("read_busy_ns", C.c_uint64)]
 
 
 class ssdt_plan_in(C.Structure):
@@ -131,6 +136,7 @@ _PROTOS = {
     "ssdt_sim_complete": (C.c_int32, [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_int32)]),
     "ssdt_sync_io": (C.c_int32, [C.c_void_p]),
     "ssdt_plan": (C.c_int32, [C.POINTER(ssdt_plan_in), C.POINTER(ssdt_plan_out)]),
+    "ssdt_spill_info": (C.c_int32, [C.c_void_p, C.POINTER(ssdt_spill_info_t)]),
     "ssdt_spill_stats": (C.c_int32, [C.c_void_p, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)]),
     "ssdt_profile": (C.c_int32, [C.c_void_p, C.c_int32]),
     "ssdt_profile_read": (C.c_int32, [C.c_void_p, C.POINTER(ssdt_kernel_time), C.c_uint32, C.POINTER(C.c_uint32)]),
@@ -183,9 +189,10 @@ def ssdt_version() -> str:
 
 
 def ssdt_ctx_create(backend=BACKEND_HIP, keep_last=1, min_offload_elems=1 << 20, budget_bytes=-1, arena_base=0,
-                    arena_bytes=0, pool_bytes=0, spill_path: Optional[str] = None, measure_waits=0) -> int:
+                    arena_bytes=0, pool_bytes=0, spill_path: Optional[str] = None, measure_waits=0,
+                    spill_threads=0) -> int:
     cfg = ssdt_config(backend, keep_last, min_offload_elems, budget_bytes, arena_base or None, arena_bytes, pool_bytes,
-                      spill_path.encode() if spill_path else None, measure_waits, 0)
+                      spill_path.encode() if spill_path else None, measure_waits, spill_threads)
     out = C.c_void_p()
     _check(None, lib().ssdt_ctx_create(C.byref(cfg), C.byref(out)), "ssdt_ctx_create")
     return out.value
@@ -306,6 +313,12 @@ def ssdt_spill_stats(ctx):
     w, r = C.c_uint64(0), C.c_uint64(0)
     _check(ctx, lib().ssdt_spill_stats(ctx, C.byref(w), C.byref(r)), "ssdt_spill_stats")
     return w.value, r.value
+
+
+def ssdt_spill_info(ctx) -> dict:
+    out = ssdt_spill_info_t()
+    _check(ctx, lib().ssdt_spill_info(ctx, C.byref(out)), "ssdt_spill_info")
+    return {n: int(getattr(out, n)) for n, _ in out._fields_}
 
 
 def ssdt_profile(ctx, enable: bool):

@@ -21,6 +21,8 @@ class HipBackend : public Backend {
     err = std::string(what) + ": " + hipGetErrorString(e);
     return false;
   }
+  int dev_ = 0;
+  void thread_init() override { (void)hipSetDevice(dev_); }
   bool init(size_t pool_bytes) {
     int n = 0;
     if (!check(hipGetDeviceCount(&n), "hipGetDeviceCount")) return false;
@@ -28,6 +30,7 @@ class HipBackend : public Backend {
       err = "no HIP device";
       return false;
     }
+    if (!check(hipGetDevice(&dev_), "hipGetDevice")) return false;
     for (int d = 0; d < 2; ++d)
       if (!check(hipStreamCreateWithFlags(&q_[d], hipStreamNonBlocking), "hipStreamCreateWithFlags")) return false;
     if (!check(hipStreamCreateWithFlags(&aux_, hipStreamNonBlocking), "hipStreamCreateWithFlags")) return false;

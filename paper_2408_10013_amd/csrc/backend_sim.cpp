@@ -89,7 +89,8 @@ class SimBackend : public Backend {
 Backend *make_sim_backend(size_t pool_bytes, std::string *err) {
   auto *b = new SimBackend();
   if (pool_bytes) {
-    b->pool_ = malloc(pool_bytes);
+    // page aligned, as pinned memory is: the spill file may be open for direct I/O
+    if (posix_memalign(&b->pool_, 4096, (pool_bytes + 4095) / 4096 * 4096) != 0) b->pool_ = nullptr;
     if (!b->pool_) {
       *err = "out of host memory for the simulated pool";
       delete b;

@@ -5,6 +5,8 @@
 #include <cstdint>
 #include <cstdio>
 #include <cstring>
+#include <atomic>
+#include <chrono>
 #include <condition_variable>
 #include <deque>
 #include <mutex>
@@ -40,6 +42,7 @@ class Backend {
   virtual ~Backend() {}
   virtual bool is_sim() const = 0;
   virtual Ev *record(ssdt_stream s, bool timing) = 0;             // event after s's current work
+  virtual void thread_init() {}                                   // called once by every helper thread that uses the backend
   virtual void wait(ssdt_stream s, Ev *e) = 0;                    // s waits for e
   virtual bool done(Ev *e) = 0;
   virtual Ev *copy(int dir, void *dst, const void *src, size_t n, Ev *after) = 0;
@@ -93,26 +96,47 @@ static inline void drop(Backend *be, Ev *e) {
   if (e && --e->refs <= 0) be->recycle(e);
 }
 
-struct WaitPair { Ev *a, *b; int kind; };
+struct WaitPair { Ev *a, *b; int kind; uint64_t step; };
 
 // Spill file: the tier behind the pinned pool (Sec. 3.1 names an SSD offloader beside the CPU
-// offloader).  The pool is the staging buffer, the file holds the data at the same offsets.  One
-// worker thread serves requests in order: a record is written once its device-to-host copy has
-// completed (its pool bytes are then overwritten with a pattern, so a later load can only come
-// from the file), and read back into the pool when a prefetch asks for it.  The host-to-device
-// copy of a record is issued by the next API call that finds its read complete.
+// offloader).  The pool is the staging buffer, the file holds the data at the same offsets.  The
+// file is opened for direct I/O (no page cache behind the pool; every tensor starts on a 4 KiB
+// boundary of pool and file when a spill file is configured) and served by a small pool of
+// threads that take requests in order, a tensor being cut into chunks so that several requests are
+// in flight at the device; each thread stages its chunk in a page-aligned buffer of its own, since
+// pinned device-visible memory cannot be the buffer of a direct transfer.  A record is written once its device-to-host
+// copy has completed (its pool bytes are then overwritten with a pattern, so a later load can
+// only come from the file), and read back into the pool when a prefetch asks for it; a read asked
+// for while the write is still going on is queued when the write ends.  The host-to-device copy
+// of a record is issued by the next API call that finds its read complete.
 struct Spill {
   int fd = -1;
-  std::thread worker;
+  bool direct = false;           // O_DIRECT in effect (false where the file system refuses it)
+  std::vector<std::thread> workers;
   std::mutex mu;
   std::condition_variable cv;
-  struct Job { int kind; size_t off, bytes; };  // kind 0 write, 1 read
-  std::deque<Job> jobs;
-  std::map<size_t, int> state;   // pool offset -> 1 write queued, 2 written, 3 read queued, 4 in pool again
-  bool busy = false, stop = false;
+  struct Chunk { int kind; size_t key, at, len; };  // kind 0 write, 1 read; key = the tensor's pool offset
+  std::deque<Chunk> chunks;
+  struct Item { int st = 0, pending = 0; bool read_wanted = false; size_t bytes = 0; };
+  std::map<size_t, Item> state;  // pool offset -> 1 write queued, 2 written, 3 read queued, 4 in pool again
+  int busy = 0;
+  bool stop = false;
   std::string error;             // first I/O error, sticky
   uint64_t bytes_written = 0, bytes_read = 0;
+  // wall time during which at least one write / read chunk was at the device
+  uint64_t write_ns = 0, read_ns = 0;
+  int writes_in_flight = 0, reads_in_flight = 0;
+  std::chrono::steady_clock::time_point w_since, r_since;
   char *pool = nullptr;
+};
+constexpr size_t kAlignSpill = 4096;       // tensor alignment in pool and file when a spill file is configured
+constexpr size_t kSpillChunk = 8u << 20;   // bytes per file request
+
+struct Ctx;
+// first statement of every C ABI entry point that takes a context
+struct ApiLock {
+  std::unique_lock<std::recursive_mutex> l;
+  explicit ApiLock(const Ctx *c);
 };
 
 struct Ctx {
@@ -144,7 +168,15 @@ struct Ctx {
   std::deque<size_t> storing;  // record indices with a store in flight, oldest first
   ssdt_stats st{};
   std::vector<WaitPair> waits;
+  uint64_t step_no = 0;  // counts ssdt_step_begin calls: wait measurements belong to the step they were taken in
   std::unique_ptr<Spill> spill;
+  // With a spill file a helper thread runs poll() a few thousand times a second, so that finished copies out of the
+  // device are written to the file, and finished file reads are copied into the device, without waiting for the
+  // caller's next call (a training loop runs a whole pass ahead of the GPU).  Every entry point of the C ABI then
+  // holds this lock for its duration; without a spill file nobody takes it.
+  mutable std::recursive_mutex api_mu;
+  std::thread pump;
+  std::atomic<bool> pump_stop{false};
   std::deque<size_t> spill_wait, reading;  // records waiting for their file write / file read
 
   ssdt_status fail(ssdt_status code, const char *fmt, ...);
@@ -176,6 +208,7 @@ struct Ctx {
   void spill_close();
   ssdt_status spill_status(const char *who);
   void spill_request(int kind, size_t pool_off, size_t bytes);
+  size_t tensor_align() const { return spill ? kAlignSpill : kAlignTensor; }
   bool spill_in_pool(size_t pool_off, bool block);
   void spill_drain();
   ssdt_status start_load(size_t idx, const char *who);

@@ -63,30 +63,34 @@ __device__ __forceinline__ bf16x8_t frag_nt(const lds_char_t *at, unsigned off) 
   return u.v;
 }
 
-template <int EPI, bool AKM, bool BKM>
-__global__ __launch_bounds__(512) void gemm_km256_k(NtP p) {
-  constexpr int MB = 8, NB = 4, NT = 512, LJ = 4;
+// W = wavefronts per workgroup: 8 (each 128 x 64 of the tile, two per SIMD) or 4 (each 128 x 128, one per SIMD with
+// the accumulators in the AGPRs: a third fewer LDS reads per MFMA, nobody to hide a stall behind).
+template <int EPI, bool AKM, bool BKM, int W>
+__global__ __launch_bounds__(W * 64) void gemm_km256_k(NtP p) {
+  constexpr int MB = 8, NB = W == 8 ? 4 : 8, NT = W * 64, LJ = 2048 / NT;
   extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
   const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), wm = wave >> 2, wn = wave & 3;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), wm = W == 8 ? wave >> 2 : wave >> 1, wn = W == 8 ? wave & 3 : wave & 1;
   int tile_m, tile_n;
   tile_of(p, blockIdx.x, &tile_m, &tile_n);
   const int m0 = tile_m * kTile, n0 = tile_n * kTile;
 
-  // ---- loader: thread t fills 16-byte LDS positions j*NT + t of each operand's buffer, j = 0..3 ----------------
-  // K-contiguous operand: position = (row j*64 + t/8, slot t%8), slot holds global chunk (t%8) ^ ((row >> 1) & 7).
-  // k-major operand: position = (k-row j*16 + t/32, 16-byte half t%2 of 32-byte unit (t%32)/2), which holds
-  // global unit ((t%32)/2) ^ key(k-row); the key does not depend on j.
+  // ---- loader: thread t fills 16-byte LDS positions j*NT + t of each operand's buffer, j = 0..LJ-1 -------------
+  // K-contiguous operand: position = (row j*NT/8 + t/8, slot t%8), slot holds global chunk (t%8) ^ ((row >> 1) & 7)
+  // (NT/8 is a multiple of 16, so the key does not depend on j).
+  // k-major operand: position = (k-row j*NT/32 + t/32, 16-byte half t%2 of 32-byte unit (t%32)/2), which holds
+  // global unit ((t%32)/2) ^ key(k-row).
   unsigned voa[LJ], vob[LJ];
   {
     const int lrow = tid >> 3, lchunk = (tid & 7) ^ ((lrow >> 1) & 7);
-    const int kr = tid >> 5, c = tid & 31, key = (kr & 3) | (((kr >> 3) & 1) << 2), unit = (c >> 1) ^ key;
+    const int c = tid & 31;
 #pragma unroll
     for (int j = 0; j < LJ; ++j) {
-      voa[j] = AKM ? (unsigned)((j * 16 + kr) * (int)p.lda) * 2u + unit * 32 + (c & 1) * 16
-                   : (unsigned)((lrow + j * 64) * (int)p.lda + lchunk * 8) * 2u;
-      vob[j] = BKM ? (unsigned)((j * 16 + kr) * (int)p.ldb) * 2u + unit * 32 + (c & 1) * 16
-                   : (unsigned)((lrow + j * 64) * (int)p.ldb + lchunk * 8) * 2u;
+      const int kr = j * (NT / 32) + (tid >> 5), key = (kr & 3) | (((kr >> 3) & 1) << 2), unit = (c >> 1) ^ key;
+      voa[j] = AKM ? (unsigned)(kr * (int)p.lda) * 2u + unit * 32 + (c & 1) * 16
+                   : (unsigned)((lrow + j * (NT / 8)) * (int)p.lda + lchunk * 8) * 2u;
+      vob[j] = BKM ? (unsigned)(kr * (int)p.ldb) * 2u + unit * 32 + (c & 1) * 16
+                   : (unsigned)((lrow + j * (NT / 8)) * (int)p.ldb + lchunk * 8) * 2u;
     }
   }
   const char *pa = (const char *)(AKM ? p.A + m0 : p.A + (long)m0 * p.lda);    // stage 0 of the tile
@@ -119,10 +123,10 @@ __global__ __launch_bounds__(512) void gemm_km256_k(NtP p) {
   }
   if (BKM) {
 #pragma unroll
-    for (int j = 0; j < NB; ++j) aB[j] = (const lds_char_t *)(uintptr_t)(lds0 + kLdsB + km_row + (unsigned)((wn * 4 + j) ^ kkey) * 32);
+    for (int j = 0; j < NB; ++j) aB[j] = (const lds_char_t *)(uintptr_t)(lds0 + kLdsB + km_row + (unsigned)((wn * NB + j) ^ kkey) * 32);
   } else {
-    aB[0] = (const lds_char_t *)(uintptr_t)(lds0 + kLdsB + (wn * 64 + lr) * 128 + nt_c0);
-    aB[1] = (const lds_char_t *)(uintptr_t)(lds0 + kLdsB + (wn * 64 + lr) * 128 + nt_c1);
+    aB[0] = (const lds_char_t *)(uintptr_t)(lds0 + kLdsB + (wn * NB * 16 + lr) * 128 + nt_c0);
+    aB[1] = (const lds_char_t *)(uintptr_t)(lds0 + kLdsB + (wn * NB * 16 + lr) * 128 + nt_c1);
   }
   // fragment of 16-row block i (of A) / j (of B) for 32-wide step `step` of the stage in buffer `buf`
   auto rdA = [&](int i, int step, int buf) -> bf16x8_t {
@@ -185,7 +189,15 @@ __global__ __launch_bounds__(512) void gemm_km256_k(NtP p) {
       if (MORE2 && i <= LJ) SSDT_LDA(BUF, pa, i - 1);                                                      \
       mfma_block(i, 1, 1, 2);                                                                              \
       if (MORE2 && i <= LJ) SSDT_LDB(BUF, pb, i - 1);                                                      \
-      mfma_block(i, 1, 2, NB);                                                                             \
+      if (LJ == MB && i == MB - 1) { /* eight loads per operand over seven blocks: the last block takes two */ \
+        mfma_block(i, 1, 2, 3);                                                                            \
+        if (MORE2) SSDT_LDA(BUF, pa, LJ - 1);                                                              \
+        mfma_block(i, 1, 3, 4);                                                                            \
+        if (MORE2) SSDT_LDB(BUF, pb, LJ - 1);                                                              \
+        mfma_block(i, 1, 4, NB);                                                                           \
+      } else {                                                                                             \
+        mfma_block(i, 1, 2, NB);                                                                           \
+      }                                                                                                    \
       if (MORE) Af[i] = rdA(i, 0, (BUF) ^ 1);                                                              \
     }                                                                                                      \
     if (MORE) {                                                                                            \
@@ -203,7 +215,9 @@ __global__ __launch_bounds__(512) void gemm_km256_k(NtP p) {
 #pragma unroll
   for (int j = 0; j < LJ; ++j) { SSDT_LDA(1, pa, j); SSDT_LDB(1, pb, j); }
   pa += sa; pb += sb;  // from here on: the stage after next
-  asm volatile("s_waitcnt vmcnt(8)" ::: "memory");  // stage 0 has landed (stage 1 may still be on its way)
+  // stage 0 has landed (stage 1, this thread's last 2 * LJ loads, may still be on its way)
+  if (LJ == 4) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+  else asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
   SSDT_FENCE;
@@ -230,51 +244,59 @@ __global__ __launch_bounds__(512) void gemm_km256_k(NtP p) {
 #undef SSDT_LDA
 #undef SSDT_LDB
 
-  // epilogue through LDS (free now), two 64x64 sub-tiles of the wavefront's 128x64: lane l of block (i, j) holds
-  // row i*16 + (l & 15), columns j*16 + (l >> 4)*4 + 0..3
-  u32x4_t ein[MB / 4][8];
-#pragma unroll
-  for (int I = 0; I < MB / 4; ++I) epilogue_fetch<EPI>(p, m0 + wm * 128 + I * 64, n0 + wn * 64, lane, ein[I]);
+  // epilogue through LDS (free now), 64x64 sub-tiles of the wavefront's part, one column of sub-tiles at a time:
+  // lane l of block (i, j) holds row i*16 + (l & 15), columns j*16 + (l >> 4)*4 + 0..3
   asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
   __builtin_amdgcn_s_barrier();  // every wavefront has finished reading the last stage
   asm volatile("" ::: "memory");
   float *stg = (float *)smem + wave * (64 * kEpiLd);
 #pragma unroll
-  for (int I = 0; I < MB / 4; ++I) {
+  for (int J = 0; J < NB / 4; ++J) {
+    const int nb = n0 + wn * NB * 16 + J * 64;
+    u32x4_t ein[MB / 4][8];  // residual / activation-input rows, all requested before the first store
 #pragma unroll
-    for (int il = 0; il < 4; ++il)
+    for (int I = 0; I < MB / 4; ++I) epilogue_fetch<EPI>(p, m0 + wm * 128 + I * 64, nb, lane, ein[I]);
 #pragma unroll
-      for (int jl = 0; jl < 4; ++jl) {
-        const f32x4_t a = acc[I * 4 + il][jl];
-        *(float4 *)(stg + (il * 16 + lr) * kEpiLd + jl * 16 + lq * 4) = make_float4(a[0], a[1], a[2], a[3]);
-      }
-    epilogue_rows<EPI>(p, stg, m0 + wm * 128 + I * 64, n0 + wn * 64, lane, ein[I]);
+    for (int I = 0; I < MB / 4; ++I) {
+#pragma unroll
+      for (int il = 0; il < 4; ++il)
+#pragma unroll
+        for (int jl = 0; jl < 4; ++jl) {
+          const f32x4_t a = acc[I * 4 + il][J * 4 + jl];
+          *(float4 *)(stg + (il * 16 + lr) * kEpiLd + jl * 16 + lq * 4) = make_float4(a[0], a[1], a[2], a[3]);
+        }
+      epilogue_rows<EPI>(p, stg, m0 + wm * 128 + I * 64, nb, lane, ein[I]);
+    }
   }
 }
 
-template <int EPI, bool AKM, bool BKM>
+int g_km_waves = 8;  // test hook: wavefronts per workgroup, 8 or 4
+
+template <int EPI, bool AKM, bool BKM, int W>
 static hipError_t launch_km(const NtP &p, hipStream_t s) {
-  constexpr size_t stg = (size_t)8 * 64 * kEpiLd * 4, stages = (size_t)4 * kBuf, smem = stg > stages ? stg : stages;
+  constexpr size_t stg = (size_t)W * 64 * kEpiLd * 4, stages = (size_t)4 * kBuf, smem = stg > stages ? stg : stages;
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void *)gemm_km256_k<EPI, AKM, BKM>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    hipError_t e = hipFuncSetAttribute((const void *)gemm_km256_k<EPI, AKM, BKM, W>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
   prof::Scope ps(prof::GEMM_MFMA_KM, 2.0 * p.M * p.N * p.K, 0, s);
-  hipLaunchKernelGGL((gemm_km256_k<EPI, AKM, BKM>), dim3(p.tiles_m * p.tiles_n), dim3(512), smem, s, p);
+  hipLaunchKernelGGL((gemm_km256_k<EPI, AKM, BKM, W>), dim3(p.tiles_m * p.tiles_n), dim3(W * 64), smem, s, p);
   return hipGetLastError();
 }
 
 template <bool AKM, bool BKM>
 static hipError_t launch_km_epi(int epi, const NtP &p, hipStream_t s) {
+#define SSDT_CASE(E) case E: return g_km_waves == 4 ? launch_km<E, AKM, BKM, 4>(p, s) : launch_km<E, AKM, BKM, 8>(p, s);
   switch (epi) {
-    case EPI_NONE: return launch_km<EPI_NONE, AKM, BKM>(p, s);
-    case EPI_BIAS: return launch_km<EPI_BIAS, AKM, BKM>(p, s);
-    case EPI_BIAS_ACT: return launch_km<EPI_BIAS_ACT, AKM, BKM>(p, s);
-    case EPI_BIAS_RESID: return launch_km<EPI_BIAS_RESID, AKM, BKM>(p, s);
-    case EPI_ACTBWD: return launch_km<EPI_ACTBWD, AKM, BKM>(p, s);
+    SSDT_CASE(EPI_NONE)
+    SSDT_CASE(EPI_BIAS)
+    SSDT_CASE(EPI_BIAS_ACT)
+    SSDT_CASE(EPI_BIAS_RESID)
+    SSDT_CASE(EPI_ACTBWD)
   }
+#undef SSDT_CASE
   return hipErrorInvalidValue;
 }
 

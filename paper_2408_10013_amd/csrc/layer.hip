@@ -134,6 +134,7 @@ ssdt_status ssdt_layer_fwd(ssdt_ctx *ctx, const ssdt_layer_desc *desc, const ssd
                            const void *x, const void *enc_out, const int32_t *kv_len, void **y_out,
                            ssdt_layer_saved *saved, void *ws, size_t ws_bytes, ssdt_stream stream) {
   if (!ctx) return SSDT_E_INVAL;
+  ApiLock api_lock_(ctx);
   Dims D;
   std::string why;
   ssdt_status s = check_desc(desc, &D, &why);
@@ -612,6 +613,7 @@ ssdt_status ssdt_layer_bwd(ssdt_ctx *ctx, const ssdt_layer_desc *desc, const ssd
                            const ssdt_layer_saved *saved, const int32_t *kv_len, const void *dy, void *dx,
                            void *d_enc_out, const ssdt_layer_weights *gr, void *ws, size_t ws_bytes,
                            ssdt_stream stream) {
+  ApiLock api_lock_(ctx);
   return layer_bwd_impl(ctx, desc, w, saved, kv_len, dy, dx, d_enc_out, gr, ws, ws_bytes, stream);
 }
 
@@ -619,6 +621,7 @@ ssdt_status ssdt_layer_bwd_static(ssdt_ctx *ctx, const ssdt_layer_desc *desc, co
                                   const ssdt_layer_saved *saved, const int32_t *kv_len, const void *dy, void *dx,
                                   void *d_enc_out, const ssdt_layer_weights *gr, ssdt_stream stream) {
   if (!ctx) return SSDT_E_INVAL;
+  ApiLock api_lock_(ctx);
   if (ctx->be->is_sim()) return ctx->fail(SSDT_E_UNSUPPORTED, "layer_bwd_static: the simulated backend has no GPU");
   size_t need = 0;
   ssdt_status s = ssdt_layer_workspace(desc, nullptr, &need);
@@ -634,6 +637,7 @@ ssdt_status ssdt_layer_bwd_static(ssdt_ctx *ctx, const ssdt_layer_desc *desc, co
 
 ssdt_status ssdt_sgd_update(ssdt_ctx *ctx, void *w, const void *g, size_t numel, int32_t dtype, float lr, ssdt_stream stream) {
   if (!ctx) return SSDT_E_INVAL;
+  ApiLock api_lock_(ctx);
   if (ctx->be->is_sim()) return ctx->fail(SSDT_E_UNSUPPORTED, "sgd_update: the simulated backend has no GPU");
   if (!w || !g || (dtype != SSDT_F32 && dtype != SSDT_BF16)) return ctx->fail(SSDT_E_INVAL, "sgd_update: null pointer or unknown dtype");
   hipError_t e = k::sgd_update(w, g, numel, lr, dtype, (hipStream_t)stream);

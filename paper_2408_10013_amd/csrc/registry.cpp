@@ -166,15 +166,15 @@ void Ctx::timed_wait(ssdt_stream s, Ev *e, int kind) {
     Ev *a = hold(be->record(s, true));
     be->wait(s, e);
     Ev *b = hold(be->record(s, true));
-    waits.push_back({a, b, kind});
+    waits.push_back({a, b, kind, step_no});
   } else {
     be->wait(s, e);
   }
 }
 
-// The store of record idx is complete (or `s` has been ordered after it): its device copy
-// is dropped (Sec. 3.2, "when the tensor finishes offloading, the tensor cache no longer
-// holds a reference to it").
+// The store of record idx is complete (or `s` has been ordered after it): the registry gives up
+// its reference on the device copy at that point (Sec. 3.2), which returns the block to the arena
+// unless someone else still holds it.
 void Ctx::reclaim(size_t idx) {
   Rec &r = recs[idx];
   bool finished = be->done(r.store_ev);
@@ -213,49 +213,118 @@ static bool rw_all(int fd, char *buf, size_t n, size_t off, bool write, std::str
   return true;
 }
 
+// Queues the chunks of one tensor's write or read (caller holds the lock).  The range is padded to whole 4 KiB
+// blocks: every tensor starts on such a boundary and owns the bytes up to the next one.
+static void spill_push(Spill *sp, int kind, size_t key, size_t bytes) {
+  Spill::Item &it = sp->state[key];
+  it.st = kind == 0 ? 1 : 3;
+  it.bytes = bytes;
+  const size_t total = up(bytes, kAlignSpill);
+  it.pending = 0;
+  for (size_t o = 0; o < total; o += kSpillChunk) {
+    sp->chunks.push_back({kind, key, key + o, std::min(kSpillChunk, total - o)});
+    ++it.pending;
+  }
+}
+
 static void spill_worker(Spill *sp) {
+  // Direct I/O cannot take pinned device-visible memory as its buffer (the kernel refuses to pin those pages a
+  // second time: EFAULT), so in direct mode every request goes through this thread's own page-aligned buffer.
+  void *bounce = nullptr;
+  if (sp->direct && posix_memalign(&bounce, kAlignSpill, kSpillChunk) != 0) bounce = nullptr;
   std::unique_lock<std::mutex> lk(sp->mu);
   for (;;) {
-    sp->cv.wait(lk, [&] { return sp->stop || !sp->jobs.empty(); });
-    if (sp->jobs.empty()) return;  // stop requested and nothing left
-    Spill::Job j = sp->jobs.front();
-    sp->jobs.pop_front();
-    sp->busy = true;
+    sp->cv.wait(lk, [&] { return sp->stop || !sp->chunks.empty(); });
+    if (sp->chunks.empty()) {  // stop requested and nothing left
+      free(bounce);
+      return;
+    }
+    Spill::Chunk c = sp->chunks.front();
+    sp->chunks.pop_front();
+    ++sp->busy;
+    const auto now = std::chrono::steady_clock::now();
+    if (c.kind == 0) { if (sp->writes_in_flight++ == 0) sp->w_since = now; }
+    else { if (sp->reads_in_flight++ == 0) sp->r_since = now; }
     bool failed = !sp->error.empty();
     lk.unlock();
     std::string err;
     bool ok = true;
     if (!failed) {
-      ok = rw_all(sp->fd, sp->pool + j.off, j.bytes, j.off, j.kind == 0, &err);
-      if (ok && j.kind == 0) memset(sp->pool + j.off, 0xEE, j.bytes);  // from here on only the file has it
+      if (sp->direct && !bounce) {
+        ok = false;
+        err = "spill: no memory for the direct-I/O buffer";
+      } else if (sp->direct) {
+        if (c.kind == 0) memcpy(bounce, sp->pool + c.at, c.len);
+        ok = rw_all(sp->fd, (char *)bounce, c.len, c.at, c.kind == 0, &err);
+        if (ok && c.kind == 1) memcpy(sp->pool + c.at, bounce, c.len);
+      } else {
+        ok = rw_all(sp->fd, sp->pool + c.at, c.len, c.at, c.kind == 0, &err);
+      }
+      if (ok && c.kind == 0) memset(sp->pool + c.at, 0xEE, c.len);  // from here on only the file has it
     }
     lk.lock();
+    const auto then = std::chrono::steady_clock::now();
+    if (c.kind == 0) { if (--sp->writes_in_flight == 0) sp->write_ns += (uint64_t)std::chrono::duration_cast<std::chrono::nanoseconds>(then - sp->w_since).count(); }
+    else { if (--sp->reads_in_flight == 0) sp->read_ns += (uint64_t)std::chrono::duration_cast<std::chrono::nanoseconds>(then - sp->r_since).count(); }
     if (!ok && sp->error.empty()) sp->error = err;
-    if (ok && !failed) (j.kind == 0 ? sp->bytes_written : sp->bytes_read) += j.bytes;
-    sp->state[j.off] = j.kind == 0 ? 2 : 4;
-    sp->busy = false;
+    Spill::Item &it = sp->state[c.key];
+    if (--it.pending == 0) {  // the tensor's last chunk
+      if (ok && !failed) (c.kind == 0 ? sp->bytes_written : sp->bytes_read) += it.bytes;
+      it.st = c.kind == 0 ? 2 : 4;
+      if (c.kind == 0 && it.read_wanted) {  // a prefetch came while the write was going on
+        it.read_wanted = false;
+        spill_push(sp, 1, c.key, it.bytes);
+      }
+    }
+    --sp->busy;
     sp->cv.notify_all();
   }
 }
 
+ApiLock::ApiLock(const Ctx *c) {
+  if (c && c->spill) l = std::unique_lock<std::recursive_mutex>(c->api_mu);
+}
+
+static void spill_pump(Ctx *c) {
+  c->be->thread_init();
+  while (!c->pump_stop.load()) {
+    std::this_thread::sleep_for(std::chrono::microseconds(200));
+    std::unique_lock<std::recursive_mutex> lk(c->api_mu, std::try_to_lock);
+    if (lk.owns_lock()) c->poll();  // what the caller's next call would do first
+  }
+}
+
 ssdt_status Ctx::spill_open(const char *path) {
-  int fd = open(path, O_RDWR | O_CREAT | O_TRUNC, 0600);
+  // direct I/O where the file system takes it: the pool is pinned memory, a second copy in the page cache would
+  // only cost host bandwidth
+  bool direct = true;
+  int fd = open(path, O_RDWR | O_CREAT | O_TRUNC | O_DIRECT, 0600);
+  if (fd < 0 && (errno == EINVAL || errno == EOPNOTSUPP || errno == ENOTSUP)) {
+    direct = false;
+    fd = open(path, O_RDWR | O_CREAT | O_TRUNC, 0600);
+  }
   if (fd < 0) return fail(SSDT_E_IO, "cannot open the spill file %s: %s", path, strerror(errno));
   spill.reset(new Spill());
   spill->fd = fd;
+  spill->direct = direct;
   spill->pool = (char *)be->pool();
-  spill->worker = std::thread(spill_worker, spill.get());
+  const int n = cfg.spill_threads > 0 ? std::min(cfg.spill_threads, 64) : 4;
+  for (int i = 0; i < n; ++i) spill->workers.emplace_back(spill_worker, spill.get());
+  pump_stop = false;
+  pump = std::thread(spill_pump, this);
   return SSDT_OK;
 }
 
 void Ctx::spill_close() {
   if (!spill) return;
+  pump_stop = true;
+  if (pump.joinable()) pump.join();
   {
     std::lock_guard<std::mutex> g(spill->mu);
     spill->stop = true;
   }
   spill->cv.notify_all();
-  spill->worker.join();
+  for (auto &t : spill->workers) t.join();
   close(spill->fd);
   spill.reset();
 }
@@ -263,8 +332,12 @@ void Ctx::spill_close() {
 void Ctx::spill_request(int kind, size_t off, size_t bytes) {
   {
     std::lock_guard<std::mutex> g(spill->mu);
-    spill->jobs.push_back({kind, off, bytes});
-    spill->state[off] = kind == 0 ? 1 : 3;
+    auto it = spill->state.find(off);
+    if (kind == 1 && it != spill->state.end() && it->second.st == 1) {
+      it->second.read_wanted = true;  // its write has not finished: the read is queued when it has
+    } else {
+      spill_push(spill.get(), kind, off, bytes);
+    }
   }
   spill->cv.notify_all();
 }
@@ -272,13 +345,13 @@ void Ctx::spill_request(int kind, size_t off, size_t bytes) {
 // True once the bytes at `off` have been read back into the pool; with `block`, waits for that.
 bool Ctx::spill_in_pool(size_t off, bool block) {
   std::unique_lock<std::mutex> lk(spill->mu);
-  if (block) spill->cv.wait(lk, [&] { return spill->state[off] == 4; });
-  return spill->state[off] == 4;
+  if (block) spill->cv.wait(lk, [&] { return spill->state[off].st == 4; });
+  return spill->state[off].st == 4;
 }
 
 void Ctx::spill_drain() {
   std::unique_lock<std::mutex> lk(spill->mu);
-  spill->cv.wait(lk, [&] { return spill->jobs.empty() && !spill->busy; });
+  spill->cv.wait(lk, [&] { return spill->chunks.empty() && spill->busy == 0; });
 }
 
 ssdt_status Ctx::spill_status(const char *who) {
@@ -396,6 +469,7 @@ ssdt_status Ctx::step_begin(int32_t n) {
   mb_keep_last.clear();
   pool_cursor = 0;
   num_layers = n;
+  ++step_no;  // measurements of earlier steps still in `waits` are dropped when they are next looked at
   ssdt_stats z{};
   st = z;
   peak_in_use = in_use;
@@ -507,7 +581,7 @@ ssdt_status Ctx::save(const void *base, size_t sbytes, size_t view_off, const in
     auto kl = mb_keep_last.find(mb_of(layer));
     bool in_last = scope_of(layer) >= num_layers - (kl != mb_keep_last.end() ? kl->second : cfg.keep_last);
     bool over = cfg.budget_bytes >= 0 && st.bytes_offloaded + sbytes > (uint64_t)cfg.budget_bytes;
-    size_t off = up(pack_cursor[layer], kAlignTensor);
+    size_t off = up(pack_cursor[layer], tensor_align());
     bool nomem = up(pack_base[layer] + off + sbytes, kAlignPack) > cfg.pool_bytes;
     const bool recomputing = !bwd_open.empty();  // a checkpointed module re-running its forward (Sec. 3.2)
     if (in_last || over || nomem || !arena || recomputing) {
@@ -721,21 +795,32 @@ ssdt_status ssdt_ctx_destroy(ssdt_ctx *ctx) {
   return SSDT_OK;
 }
 
-ssdt_status ssdt_step_begin(ssdt_ctx *c, int32_t n) { return c ? c->step_begin(n) : SSDT_E_INVAL; }
+ssdt_status ssdt_step_begin(ssdt_ctx *c, int32_t n) {
+  if (!c) return SSDT_E_INVAL;
+  ApiLock api_lock_(c);
+  return c->step_begin(n);
+}
 
-ssdt_status ssdt_micro_batch(ssdt_ctx *c, int32_t mb, int32_t keep_last) { return c ? c->micro_batch(mb, keep_last) : SSDT_E_INVAL; }
+ssdt_status ssdt_micro_batch(ssdt_ctx *c, int32_t mb, int32_t keep_last) {
+  if (!c) return SSDT_E_INVAL;
+  ApiLock api_lock_(c);
+  return c->micro_batch(mb, keep_last);
+}
 
 ssdt_status ssdt_set_budget(ssdt_ctx *c, int64_t b) {
+  ApiLock api_lock_(c);
   if (!c) return SSDT_E_INVAL;
   c->cfg.budget_bytes = b;
   return SSDT_OK;
 }
 
 ssdt_status ssdt_arena_alloc(ssdt_ctx *c, size_t bytes, ssdt_stream s, void **out) {
+  ApiLock api_lock_(c);
   return c ? c->alloc(bytes, s, out) : SSDT_E_INVAL;
 }
 
 ssdt_status ssdt_arena_free(ssdt_ctx *c, void *p, ssdt_stream s) {
+  ApiLock api_lock_(c);
   if (!c) return SSDT_E_INVAL;
   if (!p || !c->in_arena(p)) return c->fail(SSDT_E_INVAL, "arena_free: pointer is not inside the arena");
   auto it = c->blocks.find((char *)p - (char *)c->cfg.arena_base);
@@ -752,34 +837,63 @@ ssdt_status ssdt_arena_free(ssdt_ctx *c, void *p, ssdt_stream s) {
 }
 
 ssdt_status ssdt_register_weight(ssdt_ctx *c, const void *base, size_t bytes) {
+  ApiLock api_lock_(c);
   if (!c) return SSDT_E_INVAL;
   if (!base || !bytes) return c->fail(SSDT_E_INVAL, "register_weight: null or empty buffer");
   c->weights.emplace_back((const char *)base, bytes);
   return SSDT_OK;
 }
 
-ssdt_status ssdt_scope_begin(ssdt_ctx *c, int32_t scope, int32_t phase) { return c ? c->scope_begin(scope, phase) : SSDT_E_INVAL; }
-ssdt_status ssdt_scope_end(ssdt_ctx *c, int32_t scope, int32_t phase) { return c ? c->scope_end(scope, phase) : SSDT_E_INVAL; }
+ssdt_status ssdt_scope_begin(ssdt_ctx *c, int32_t scope, int32_t phase) {
+  if (!c) return SSDT_E_INVAL;
+  ApiLock api_lock_(c);
+  return c->scope_begin(scope, phase);
+}
+ssdt_status ssdt_scope_end(ssdt_ctx *c, int32_t scope, int32_t phase) {
+  if (!c) return SSDT_E_INVAL;
+  ApiLock api_lock_(c);
+  return c->scope_end(scope, phase);
+}
 
 ssdt_status ssdt_save(ssdt_ctx *c, const void *base, size_t sbytes, size_t off, const int64_t *shape, int32_t ndim,
                       int32_t dtype, ssdt_tid *out) {
+  ApiLock api_lock_(c);
   return c ? c->save(base, sbytes, off, shape, ndim, dtype, out) : SSDT_E_INVAL;
 }
 
-ssdt_status ssdt_offload(ssdt_ctx *c, int32_t scope, ssdt_stream p) { return c ? c->offload(scope, p) : SSDT_E_INVAL; }
-ssdt_status ssdt_prefetch(ssdt_ctx *c, int32_t scope) { return c ? c->prefetch(scope) : SSDT_E_INVAL; }
-ssdt_status ssdt_get(ssdt_ctx *c, ssdt_tid t, ssdt_stream s, void **out) { return c ? c->get(t, s, out) : SSDT_E_INVAL; }
-ssdt_status ssdt_release(ssdt_ctx *c, int32_t scope, ssdt_stream s) { return c ? c->release(scope, s) : SSDT_E_INVAL; }
+ssdt_status ssdt_offload(ssdt_ctx *c, int32_t scope, ssdt_stream p) {
+  if (!c) return SSDT_E_INVAL;
+  ApiLock api_lock_(c);
+  return c->offload(scope, p);
+}
+ssdt_status ssdt_prefetch(ssdt_ctx *c, int32_t scope) {
+  if (!c) return SSDT_E_INVAL;
+  ApiLock api_lock_(c);
+  return c->prefetch(scope);
+}
+ssdt_status ssdt_get(ssdt_ctx *c, ssdt_tid t, ssdt_stream s, void **out) {
+  if (!c) return SSDT_E_INVAL;
+  ApiLock api_lock_(c);
+  return c->get(t, s, out);
+}
+ssdt_status ssdt_release(ssdt_ctx *c, int32_t scope, ssdt_stream s) {
+  if (!c) return SSDT_E_INVAL;
+  ApiLock api_lock_(c);
+  return c->release(scope, s);
+}
 
 ssdt_status ssdt_get_stats(ssdt_ctx *c, ssdt_stats *out) {
+  ApiLock api_lock_(c);
   if (!c || !out) return SSDT_E_INVAL;
   // fold in the wait measurements whose closing event has completed
   for (size_t i = 0; i < c->waits.size();) {
     WaitPair w = c->waits[i];
     if (c->be->done(w.b)) {
-      double ms = c->be->elapsed_ms(w.a, w.b);
-      uint64_t ns = ms > 0 ? (uint64_t)(ms * 1e6) : 0;
-      (w.kind == 0 ? c->st.exposed_load_wait_ns : c->st.exposed_store_wait_ns) += ns;
+      if (w.step == c->step_no) {  // the counters are per step, like every other one
+        double ms = c->be->elapsed_ms(w.a, w.b);
+        uint64_t ns = ms > 0 ? (uint64_t)(ms * 1e6) : 0;
+        (w.kind == 0 ? c->st.exposed_load_wait_ns : c->st.exposed_store_wait_ns) += ns;
+      }
       if (--w.a->refs <= 0) c->be->recycle(w.a);
       if (--w.b->refs <= 0) c->be->recycle(w.b);
       c->waits[i] = c->waits.back();
@@ -797,12 +911,14 @@ ssdt_status ssdt_get_stats(ssdt_ctx *c, ssdt_stats *out) {
 }
 
 ssdt_status ssdt_num_records(const ssdt_ctx *c, uint32_t *out) {
+  ApiLock api_lock_(c);
   if (!c || !out) return SSDT_E_INVAL;
   *out = (uint32_t)c->recs.size();
   return SSDT_OK;
 }
 
 ssdt_status ssdt_get_record(const ssdt_ctx *c, uint32_t i, ssdt_record *out) {
+  ApiLock api_lock_(c);
   if (!c || !out) return SSDT_E_INVAL;
   if (i >= c->recs.size()) return SSDT_E_NOTFOUND;
   const Rec &r = c->recs[i];
@@ -821,6 +937,7 @@ ssdt_status ssdt_get_record(const ssdt_ctx *c, uint32_t i, ssdt_record *out) {
 }
 
 ssdt_status ssdt_pool_read(ssdt_ctx *c, size_t off, void *dst, size_t bytes) {
+  ApiLock api_lock_(c);
   if (!c || !dst) return SSDT_E_INVAL;
   if (off + bytes > c->cfg.pool_bytes) return c->fail(SSDT_E_INVAL, "pool_read: range outside the pool");
   c->be->sync_io();
@@ -828,8 +945,15 @@ ssdt_status ssdt_pool_read(ssdt_ctx *c, size_t off, void *dst, size_t bytes) {
     c->poll();
     c->spill_drain();
     if (ssdt_status e = c->spill_status("pool_read")) return e;
+    // the file may be open for direct I/O: read whole 4 KiB blocks into an aligned buffer
+    const size_t lo = off / kAlignSpill * kAlignSpill, hi = up(off + bytes, kAlignSpill);
+    void *tmp = nullptr;
+    if (posix_memalign(&tmp, kAlignSpill, hi - lo) != 0) return c->fail(SSDT_E_NOMEM, "pool_read: no memory");
     std::string err;
-    if (!rw_all(c->spill->fd, (char *)dst, bytes, off, false, &err)) return c->fail(SSDT_E_IO, "pool_read: %s", err.c_str());
+    const bool ok = rw_all(c->spill->fd, (char *)tmp, hi - lo, lo, false, &err);
+    if (ok) memcpy(dst, (char *)tmp + (off - lo), bytes);
+    free(tmp);
+    if (!ok) return c->fail(SSDT_E_IO, "pool_read: %s", err.c_str());
     return SSDT_OK;
   }
   memcpy(dst, (char *)c->be->pool() + off, bytes);
@@ -837,6 +961,7 @@ ssdt_status ssdt_pool_read(ssdt_ctx *c, size_t off, void *dst, size_t bytes) {
 }
 
 ssdt_status ssdt_sim_complete(ssdt_ctx *c, int32_t dir, int32_t n, int32_t *done) {
+  ApiLock api_lock_(c);
   if (!c) return SSDT_E_INVAL;
   int k = c->be->sim_complete(dir, n);
   if (k < 0) return c->fail(SSDT_E_UNSUPPORTED, "sim_complete: not the simulated backend");
@@ -845,6 +970,7 @@ ssdt_status ssdt_sim_complete(ssdt_ctx *c, int32_t dir, int32_t n, int32_t *done
 }
 
 ssdt_status ssdt_profile(ssdt_ctx *c, int32_t enable) {
+  ApiLock api_lock_(c);
   if (!c) return SSDT_E_INVAL;
   if (c->be->is_sim()) return c->fail(SSDT_E_UNSUPPORTED, "profile: the simulated backend launches no kernels");
   if (enable) prof::reset();
@@ -853,6 +979,7 @@ ssdt_status ssdt_profile(ssdt_ctx *c, int32_t enable) {
 }
 
 ssdt_status ssdt_profile_read(ssdt_ctx *c, ssdt_kernel_time *out, uint32_t cap, uint32_t *n) {
+  ApiLock api_lock_(c);
   if (!c || !out || !n) return SSDT_E_INVAL;
   if (c->be->is_sim()) return c->fail(SSDT_E_UNSUPPORTED, "profile: the simulated backend launches no kernels");
   prof::collect();
@@ -871,6 +998,7 @@ ssdt_status ssdt_profile_read(ssdt_ctx *c, ssdt_kernel_time *out, uint32_t cap, 
 }
 
 ssdt_status ssdt_sync_io(ssdt_ctx *c) {
+  ApiLock api_lock_(c);
   if (!c) return SSDT_E_INVAL;
   c->be->sync_io();
   c->poll();
@@ -882,7 +1010,22 @@ ssdt_status ssdt_sync_io(ssdt_ctx *c) {
   return SSDT_OK;
 }
 
+ssdt_status ssdt_spill_info(ssdt_ctx *c, ssdt_spill_info_t *out) {
+  ApiLock api_lock_(c);
+  if (!c || !out) return SSDT_E_INVAL;
+  if (!c->spill) return c->fail(SSDT_E_STATE, "spill_info: the context has no spill file");
+  std::lock_guard<std::mutex> g(c->spill->mu);
+  out->direct_io = c->spill->direct ? 1 : 0;
+  out->threads = (int32_t)c->spill->workers.size();
+  out->bytes_written = c->spill->bytes_written;
+  out->bytes_read = c->spill->bytes_read;
+  out->write_busy_ns = c->spill->write_ns;
+  out->read_busy_ns = c->spill->read_ns;
+  return SSDT_OK;
+}
+
 ssdt_status ssdt_spill_stats(ssdt_ctx *c, uint64_t *bytes_written, uint64_t *bytes_read) {
+  ApiLock api_lock_(c);
   if (!c) return SSDT_E_INVAL;
   if (!c->spill) return c->fail(SSDT_E_STATE, "spill_stats: the context has no spill file");
   std::lock_guard<std::mutex> g(c->spill->mu);

@@ -82,7 +82,7 @@ class Stack:
     """A stack of layers on one GPU with its tensor-cache context."""
 
     def __init__(self, layers: List[Layer], arena_bytes: int, pool_bytes: int, device="cuda:0", keep_last=1,
-                 min_offload_elems=1 << 20, budget_bytes=-1, measure_waits=0, spill_path=None):
+                 min_offload_elems=1 << 20, budget_bytes=-1, measure_waits=0, spill_path=None, spill_threads=0):
         self.layers = layers
         self.dev = torch.device(device)
         self.dtype = layers[0].dtype
@@ -93,7 +93,8 @@ class Stack:
         self.ctx = sb.ssdt_ctx_create(backend=sb.BACKEND_HIP, keep_last=keep_last, min_offload_elems=min_offload_elems,
                                       budget_bytes=budget_bytes, arena_base=self.arena_base,
                                       arena_bytes=arena_bytes - (self.arena_base - base), pool_bytes=pool_bytes,
-                                      measure_waits=measure_waits, spill_path=spill_path)
+                                      measure_waits=measure_waits, spill_path=spill_path,
+                                      spill_threads=spill_threads)
         fb = bb = 0
         for l in layers:
             f, b = sb.ssdt_layer_workspace(l.desc)

@@ -44,25 +44,31 @@ def device_weights(layers, seed):
     return gen, out
 
 
-def run_stack(cfg, weights, x, dy, enc_x, kv, *, offload, arena_layers, capture):
+def run_stack(cfg, weights, x, dy, enc_x, kv, *, offload, arena_layers, capture, spill_path=None, settle=False):
     layers = runner.layers_from_config(cfg)
     for l, w in zip(layers, weights):
         l.set_weights(w)
     per = max(runner.saved_bytes_per_layer(l) for l in layers)
     pool = runner.pool_bytes_needed(layers, keep_last=0) if offload else 0
     st = runner.Stack(layers, int(arena_layers * per) + (64 << 20), pool, DEV, keep_last=0, min_offload_elems=1 << 20,
-                      budget_bytes=-1 if offload else 0)
+                      budget_bytes=-1 if offload else 0, spill_path=spill_path)
     st.register_weights()
     if capture:
         st.capture = {}
     yp = st.forward(x, enc_x=enc_x, kv_len=kv)
     y = st.view(yp, tuple(x.shape)).clone()
     recs = st.records()
+    if settle:          # let every store (and file write) finish before backward asks for anything back
+        torch.cuda.synchronize()
+        sb.ssdt_sync_io(st.ctx)
     dx, dxe = st.backward(dy)
     torch.cuda.synchronize()
     sb.ssdt_arena_free(st.ctx, yp, st.stream)
     out = dict(y=y, dx=dx.clone(), dxe=None if dxe is None else dxe.clone(), layers=layers, stats=st.stats(), recs=recs,
                grads=[{k: v.clone() for k, v in l.g.items()} for l in layers], cap=st.capture)
+    if spill_path:
+        sb.ssdt_sync_io(st.ctx)
+        out["spill"] = sb.ssdt_spill_info(st.ctx)
     st.close()
     return out
 
@@ -164,3 +170,30 @@ def test_benchmark_shape_offload_on_equals_off_bit_for_bit():
     assert float(on["dx"].float().abs().max()) > 0 and all(float(g["w_1"].float().abs().max()) > 0 for g in on["grads"])
     print("gpt_8192 x3 B=16 on/off identical; loads %d forwarded %d arena peak %.1f vs %.1f GB" % (
         s["loads"], s["forwarded"], s["arena_peak_in_use"] / 1e9, off["stats"]["arena_peak_in_use"] / 1e9))
+
+
+def test_file_tier_at_the_benchmark_layer_shape(tmp_path):
+    """Three gpt_8192 layers (full width, micro-batch 4: 2.1 GB of saved tensors each) offloaded through the pinned pool
+    into a spill file with an arena that cannot keep them: every tensor that is reloaded comes from the file (its pool
+    bytes are overwritten once written), in several direct-I/O requests each.  Outputs and gradients must be the same
+    bits as with the pool alone."""
+    cfg = dict(synth.CONFIGS["gpt_8192"], stack=[("gpt_preln", 3)], B=4)
+    dev = torch.device(DEV)
+    proto = runner.layers_from_config(cfg)
+    gen, weights = device_weights(proto, synth.BASE_SEED + 460)
+    x = torch.randn(proto[0].T, proto[0].H, generator=gen, device=dev).to(torch.bfloat16)
+    dy = torch.randn(proto[0].T, proto[0].H, generator=gen, device=dev).to(torch.bfloat16)
+    # The host enqueues a whole pass ahead of the GPU, and a tensor whose copy out has not been seen finished when it
+    # is asked back is served from the pool; so both runs wait for their stores between forward and backward, after
+    # which the file run has nothing but the file to load from.
+    pool = run_stack(cfg, weights, x, dy, None, None, offload=True, arena_layers=2.5, capture=False, settle=True)
+    file = run_stack(cfg, weights, x, dy, None, None, offload=True, arena_layers=2.5, capture=False, settle=True,
+                     spill_path=str(tmp_path / "spill.bin"))
+    assert_identical(pool, file)
+    s, si = file["stats"], file["spill"]
+    assert s["loads"] > 0 and s["loads"] + s["forwarded"] == s["offloaded"] == 3 * 8
+    assert s["forwarded"] == 0 and si["bytes_read"] == s["bytes_loaded"] == si["bytes_written"] == s["bytes_offloaded"]
+    assert si["bytes_read"] >= 1 << 30                      # whole activations came back from the file
+    print("file tier: direct I/O %d, %d threads, wrote %.2f GB at %.2f GB/s, read %.2f GB at %.2f GB/s" % (
+        si["direct_io"], si["threads"], si["bytes_written"] / 1e9, si["bytes_written"] / max(1, si["write_busy_ns"]),
+        si["bytes_read"] / 1e9, si["bytes_read"] / max(1, si["read_busy_ns"])))

@@ -105,6 +105,125 @@ def test_plan_is_feasible_and_maximal_on_small_cases():
             assert (not stores_fit) or (not loads_fit) or cut_back, (lb, fwd, w, r, keep, p)
 
 
+def test_unequal_layers_worked_by_hand():
+    """Two cases with layers of different lengths and sizes, worked on paper from the rules (stores: one queue in
+    forward order, a layer's bytes available when its forward ends, counted only if gone by the end of forward;
+    loads: one queue in reverse order, layer l issued when backward of layer l+d starts, due when backward of layer l
+    starts).  Both the reference and the library must give the paper result."""
+    # (A) forward 1, 2, 1 s (ends at 1, 3, 4), backward 2, 4, 2 s; 8, 4, 6 bytes; store 4 B/s, load 2 B/s; last kept.
+    #     stores: layer 0 from 1 s to 3 s; layer 1 from 3 s to 4 s = end of forward: both whole, 12 bytes, done at 4 s.
+    #     backward starts: layer 2 at 4 s, layer 1 at 6 s, layer 0 at 10 s.  distance 1: layer 1 issued at 4 s, 2 s
+    #     long, done at 6 s (due 6 s); layer 0 issued at 6 s, 4 s long, done at 10 s (due 10 s): hidden.
+    a = ([8, 4, 6], [1.0, 2.0, 1.0], [2.0, 4.0, 2.0], 4.0, 2.0, 1.0, 1)
+    want_a = (12, 2, 0, 1, 4.0)
+    # (B) forward 2, 1, 1, 2 s (ends at 2, 3, 4, 6), backward 4, 2, 2, 4 s; 6, 8, 4, 10 bytes; store 2 B/s; last kept.
+    #     stores: layer 0 from 2 s to 5 s; layer 1 starts at 5 s and would need 4 s: (6 - 5) s * 2 B/s = 2 bytes count;
+    #     amount 6 + 2, last store done at 6 s.  backward starts: layer 3 at 6 s, 2 at 10 s, 1 at 12 s, 0 at 14 s.
+    #     load 1 B/s: distance 1: layer 1 (2 B) issued at 10 s, done 12 s; layer 0 (6 B) issued at 12 s, done 18 s > 14 s.
+    #     distance 2: layer 1 issued at 6 s, done 8 s; layer 0 issued at 10 s, done 16 s > 14 s.  distance 3: layer 1
+    #     issued at the end of forward (6 s), done 8 s; layer 0 issued at 6 s, waits for the queue, 8 s .. 14 s: hidden.
+    b1 = ([6, 8, 4, 10], [2.0, 1.0, 1.0, 2.0], [4.0, 2.0, 2.0, 4.0], 2.0, 1.0, 1.0, 1)
+    want_b1 = (8, 1, 2, 3, 6.0)
+    #     load 0.75 B/s: layer 1 takes 2.67 s, layer 0 8 s: even issued together at 6 s they end at 16.67 s > 14 s, so
+    #     the partial layer is given up; layer 0 alone: issued at 12 s (distance 1) or 10 s (distance 2) it is late,
+    #     issued at 6 s (distance 3) it is done at 14 s: hidden.  Its store is done at 5 s.
+    b2 = ([6, 8, 4, 10], [2.0, 1.0, 1.0, 2.0], [4.0, 2.0, 2.0, 4.0], 2.0, 0.75, 1.0, 1)
+    want_b2 = (6, 1, 0, 3, 5.0)
+    for args, want in ((a, want_a), (b1, want_b1), (b2, want_b2)):
+        p = po.plan(*args)
+        assert (p.budget_bytes, p.layers, p.partial_bytes, p.prefetch_distance, p.store_done_s) == want, (args, p)
+        g = sb.ssdt_plan(*args)
+        assert (g["budget_bytes"], g["layers"], g["partial_bytes"], g["prefetch_distance"], g["store_done_s"]) == want, (args, g)
+
+
+class Timeline:
+    """The rules of the planner played out tick by tick (1/64 s), with no arithmetic shared with the reference or the
+    library: a store queue that moves `w` bytes per second of the oldest unfinished layer once that layer's forward
+    has ended, a load queue that moves `r` bytes per second of the oldest issued request.  All quantities in the
+    tests that use it are dyadic, so every comparison is exact."""
+    TICK = 1.0 / 64
+
+    def __init__(self, fwd_s, bwd_s):
+        self.n = len(fwd_s)
+        self.fwd_end = [sum(fwd_s[:l + 1]) for l in range(self.n)]
+        self.t_fwd = self.fwd_end[-1]
+        self.bwd_start = {}
+        t = self.t_fwd
+        for l in range(self.n - 1, -1, -1):
+            self.bwd_start[l] = t
+            t += bwd_s[l]
+        self.t_end = t
+
+    def drained_by_end_of_forward(self, layer_bytes, eligible, w):
+        """Bytes of each eligible layer that have left the device when the forward pass ends (whole bytes)."""
+        left = [float(b) for b in layer_bytes[:eligible]]
+        t = 0.0
+        while t < self.t_fwd:
+            for l in range(eligible):
+                if left[l] > 0:
+                    if self.fwd_end[l] <= t:          # available during this whole tick
+                        left[l] = max(0.0, left[l] - w * self.TICK)
+                    break                             # first in, first out: nobody overtakes
+            t += self.TICK
+        out = []
+        for l in range(eligible):
+            gone = int(layer_bytes[l] - left[l])
+            if gone <= 0:
+                break
+            out.append(gone)
+            if left[l] > 0:
+                break
+        return out
+
+    def loads_hidden(self, amount, r, d):
+        left = {l: float(a) for l, a in enumerate(amount)}
+        order = sorted(left, reverse=True)
+        issue = {l: (self.bwd_start[l + d] if l + d < self.n else self.t_fwd) for l in order}
+        t = self.t_fwd
+        while t < self.t_end:
+            for l in order:
+                if left[l] > 0 and t >= self.bwd_start[l]:
+                    return False                      # its backward starts and it is not back
+            for l in order:
+                if left[l] > 0:
+                    if issue[l] <= t:
+                        left[l] = max(0.0, left[l] - r * self.TICK)
+                    break
+            t += self.TICK
+        return all(v <= 0 for v in left.values())
+
+
+def test_library_plan_against_the_tick_by_tick_timeline():
+    """ssdt_plan's own output on 200 seeded dyadic cases: what it offloads is exactly what the store queue drains by
+    the end of forward, cut back from the top only as far as the loads demand, with the smallest prefetch distance
+    that hides them."""
+    rng = np.random.default_rng(17)
+    seen_cut = seen_far = 0
+    for _ in range(200):
+        n = int(rng.integers(2, 6))
+        fwd = [int(rng.integers(1, 9)) / 8 for _ in range(n)]
+        bwd = [2 * f for f in fwd]
+        lb = [int(rng.integers(1, 9)) * 64 for _ in range(n)]
+        w = float(2 ** int(rng.integers(5, 10)))
+        r = float(2 ** int(rng.integers(4, 10)))
+        keep = int(rng.integers(0, 2))
+        g = sb.ssdt_plan(lb, fwd, bwd, w, r, 1.0, keep)
+        got = lb[:g["layers"]] + ([g["partial_bytes"]] if g["partial_bytes"] else [])
+        assert sum(got) == g["budget_bytes"]
+        tl = Timeline(fwd, bwd)
+        prefix = tl.drained_by_end_of_forward(lb, n - keep, w)
+        want, want_d = [], 0
+        for k in range(len(prefix), 0, -1):          # give up the partial layer first, then layers from the top
+            ds = [d for d in range(1, n + 1) if tl.loads_hidden(prefix[:k], r, d)]
+            if ds:
+                want, want_d = prefix[:k], ds[0]
+                break
+        assert got == want and g["prefetch_distance"] == want_d, (lb, fwd, w, r, keep, g, prefix, want, want_d)
+        seen_cut += len(want) < len(prefix)
+        seen_far += want_d > 1
+    assert seen_cut >= 5 and seen_far >= 5           # the cases do exercise both rules
+
+
 # ---- the library against the reference ---------------------------------------------------------------
 
 def cases():

@@ -374,6 +374,53 @@ def test_spill_file_is_the_store_and_reloads_are_bit_identical(tmp_path):
     sb.ssdt_ctx_destroy(ctx)
 
 
+def test_spill_layout_is_block_aligned_and_io_is_chunked(tmp_path):
+    """With a spill file every tensor starts on a 4096-byte boundary of pool and file (the bookkeeping checker with
+    tensor_align = 4096 gives the same offsets), the file is served by the configured number of threads, and a tensor
+    larger than one request (8 MiB) is written and read back in several chunks, bit for bit."""
+    big = (20 << 20) + 1024                                  # three requests, the last one short and padded
+    ar = Arena((64 << 20) + 4096)
+    ctx = sb.ssdt_ctx_create(backend=sb.BACKEND_SIM, keep_last=0, min_offload_elems=0, budget_bytes=-1,
+                             arena_base=ar.base, arena_bytes=64 << 20, pool_bytes=48 << 20,
+                             spill_path=str(tmp_path / "big.bin"), spill_threads=3)
+    info = sb.ssdt_spill_info(ctx)
+    assert info["threads"] == 3 and info["direct_io"] in (0, 1)
+    sizes = [1024, big, 768, 4096]
+    rng = np.random.default_rng(3)
+    sb.ssdt_step_begin(ctx, 1)
+    sb.ssdt_scope_begin(ctx, 0)
+    tids, data = [], []
+    reg = ro.RegistryOracle(1, 0, None, 0, 48 << 20, tensor_align=4096)
+    reg.scope_begin(0)
+    for i, n in enumerate(sizes):
+        p = sb.ssdt_arena_alloc(ctx, n)
+        blob = rng.integers(0, 256, n, dtype=np.uint8)
+        ar.view(p, n)[:] = blob
+        data.append(blob.tobytes())
+        tids.append(sb.ssdt_save(ctx, p, n, 0, [n // 4], sb.F32))
+        reg.save(("t", i), n, n // 4)
+        sb.ssdt_arena_free(ctx, p)
+    sb.ssdt_scope_end(ctx, 0)
+    reg.scope_end(0)
+    recs = records(ctx)
+    assert [(r["pack_offset"], r["pool_offset"]) for r in recs] == [(r.pack_offset, r.pool_offset) for r in reg.records]
+    assert all(r["pool_offset"] % 4096 == 0 for r in recs)
+    sb.ssdt_offload(ctx, 0)
+    assert sb.ssdt_sim_complete(ctx, 0, 4) == 4
+    sb.ssdt_sync_io(ctx)                                     # copies done, all four written
+    for r, blob in zip(recs, data):                          # the file holds them; the pool copies are gone
+        assert sb.ssdt_pool_read(ctx, r["pool_offset"], r["bytes"]) == blob
+    sb.ssdt_prefetch(ctx, 0)
+    for t, blob in zip(tids, data):
+        p = sb.ssdt_get(ctx, t)
+        assert bytes(ar.view(p, len(blob))) == blob
+    info = sb.ssdt_spill_info(ctx)
+    assert info["bytes_written"] == sum(sizes) and info["bytes_read"] == sum(sizes)
+    assert info["write_busy_ns"] > 0 and info["read_busy_ns"] > 0
+    sb.ssdt_release(ctx, 0)
+    sb.ssdt_ctx_destroy(ctx)
+
+
 def test_spill_release_before_the_read_was_used_and_demand_load(tmp_path):
     ctx, ar = make(arena_bytes=1 << 16, spill_path=str(tmp_path / "s.bin"))
     fill = {n: ord(n) for n in "abcdef"}
