@@ -206,15 +206,24 @@ __global__ __launch_bounds__(W * 64) void gemm_km256_k(NtP p) {
       SSDT_FENCE;                                                                                          \
     }                                                                                                      \
     pa += sa; pb += sb;                                                                                    \
+    if (++cur == nk) { cur = 0; pa -= wrap_a; pb -= wrap_b; }                                              \
   }
 
   const int nk = p.K / kStageK;  // even, >= 2 (checked by the launcher)
+  // The K loop may start at a stage other than 0 and wrap around (every workgroup of an XCD at the same stage, so
+  // that they still share their panels in the L2; the XCDs apart from each other).
+  const int s0 = __builtin_amdgcn_readfirstlane((int)((blockIdx.x & 7) * p.stagger) % nk) & ~1;
+  const long wrap_a = (long)nk * sa, wrap_b = (long)nk * sb;
+  pa += (long)s0 * sa; pb += (long)s0 * sb;
+  int cur = s0;
 #pragma unroll
   for (int j = 0; j < LJ; ++j) { SSDT_LDA(0, pa, j); SSDT_LDB(0, pb, j); }
   pa += sa; pb += sb;
+  if (++cur == nk) { cur = 0; pa -= wrap_a; pb -= wrap_b; }
 #pragma unroll
   for (int j = 0; j < LJ; ++j) { SSDT_LDA(1, pa, j); SSDT_LDB(1, pb, j); }
   pa += sa; pb += sb;  // from here on: the stage after next
+  if (++cur == nk) { cur = 0; pa -= wrap_a; pb -= wrap_b; }
   // stage 0 has landed (stage 1, this thread's last 2 * LJ loads, may still be on its way)
   if (LJ == 4) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
   else asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
@@ -271,6 +280,7 @@ __global__ __launch_bounds__(W * 64) void gemm_km256_k(NtP p) {
 }
 
 int g_km_waves = 8;  // test hook: wavefronts per workgroup, 8 or 4
+int g_km_stagger = -100;  // test hook: stages between the K-loop starting points of neighbouring XCDs (-100 = by shape, -1 = K/8, -2 = K/16)
 
 template <int EPI, bool AKM, bool BKM, int W>
 static hipError_t launch_km(const NtP &p, hipStream_t s) {
@@ -304,11 +314,22 @@ int g_km_mode = 1;  // test hook: 0 = never use this kernel, 1 = for k-major ope
 
 // Shape part of the conditions below: what a caller can know before it has pointers (workspace sizing, the choice
 // between this kernel and transposed copies).
+// Staggered K loops pay where many column tiles share a short K (measured on 32768 x N x 8192: +4 % at N = 24576
+// and 32768, nothing at N = 8192; with K = 32768 nothing or a small loss): there all XCDs sweep the same B panels
+// at the same K offset, and starting them K/8 apart spreads those reads over the memory channels.
+static int stagger_for(int N, int K) {
+  if (g_km_stagger != -100) return g_km_stagger >= 0 ? g_km_stagger : (K / kStageK) / (4 << -g_km_stagger);
+  const int nk = K / kStageK;
+  return (nk <= 128 && N / kTile >= 64) ? nk / 8 : 0;
+}
+
 bool gemm_km_fits(int M, int N, int K, bool transA, bool transB, int dtype) {
   if (dtype != SSDT_BF16 || g_km_mode == 0) return false;
-  if (!transA && transB && g_km_mode < 2) return false;
   if (M % kTile || N % kTile || K % (2 * kStageK) || K < 2 * kStageK) return false;
-  return (long)(M / kTile) * (N / kTile) >= 256;
+  if ((long)(M / kTile) * (N / kTile) < 256) return false;
+  // the K-contiguous form stays with gemm_nt256_k unless this kernel's staggered K loop pays for the shape
+  if (!transA && transB && g_km_mode < 2 && stagger_for(N, K) == 0) return false;
+  return true;
 }
 
 // Takes the problem if it fits (hipErrorNotSupported otherwise, nothing launched): bf16, M and N multiples of 256 with
@@ -328,7 +349,8 @@ hipError_t gemm_mfma_km_bf16(const Gemm &g, hipStream_t s) {
   if ((akm && g.lda < g.M) || (bkm && g.ldb < g.N)) return hipErrorInvalidValue;
   NtP p{g.M, g.N, g.K, (const uint16_t *)g.A, (const uint16_t *)g.B, g.lda, g.ldb, g.ldc, g.ldr, (uint16_t *)g.C,
         (uint16_t *)g.C2, (const uint16_t *)g.bias, (const uint16_t *)g.resid, (const uint16_t *)g.aux, g.act,
-        g.M / kTile, g.N / kTile, 8};
+        g.M / kTile, g.N / kTile, 8, 0};
+  p.stagger = stagger_for(g.N, g.K);
   p.gm = g_force_waves > 0 ? g_force_waves : (p.tiles_m >= p.tiles_n ? 4 : 8);
   if (akm && bkm) return launch_km_epi<true, true>(g.epi, p, s);
   if (bkm) return launch_km_epi<false, true>(g.epi, p, s);

@@ -19,6 +19,7 @@ struct NtP {
   uint16_t *C, *C2;
   const uint16_t *bias, *resid, *aux;
   int act, tiles_m, tiles_n, gm;
+  int stagger;  // gemm_km256_k: the workgroups of XCD x start their K loop x * stagger stages in (0 = all at stage 0)
 };
 
 __device__ __forceinline__ void unpack4(uint2 v, float *f) {
