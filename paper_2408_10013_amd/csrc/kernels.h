@@ -40,6 +40,10 @@ struct Gemm {
   const void *aux = nullptr;    // [M, ldc]
   int act = SSDT_ACT_GELU;
   int dtype = SSDT_F32;
+  void *colsum = nullptr;       // [N] or null: sum over k of B(k, n), taken from the operand fragments while they pass
+                                // through the registers.  Only gemm_mfma_km_bf16 can do this; every other path
+                                // returns hipErrorNotSupported (nothing launched) when it is set.
+  bool colsum_accumulate = false;  // add to what colsum holds
   void *scratch = nullptr;      // optional: room for transposed copies of operands (bf16 fast path)
   size_t scratch_bytes = 0;
 };
@@ -120,7 +124,6 @@ hipError_t gemm_mfma_bf16(const Gemm &g, hipStream_t s);
 hipError_t gemm_mfma_km_bf16(const Gemm &g, hipStream_t s);  // reads k-major operands as stored; no scratch
 bool gemm_km_fits(int M, int N, int K, bool transA, bool transB, int dtype);  // shape conditions of that kernel
 extern int g_km_stagger;
-extern int g_km_waves;  // 8 (default) or 4 wavefronts per workgroup of that kernel
 extern int g_km_mode;  // 0 = off, 1 = for problems with a k-major operand (default), 2 = also for the NT form
 hipError_t attn_fwd_mfma_bf16(const Attn &a, hipStream_t s);
 hipError_t attn_bwd_mfma_bf16(const Attn &a, hipStream_t s);

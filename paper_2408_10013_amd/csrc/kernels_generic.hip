@@ -121,6 +121,7 @@ hipError_t gemm_generic(const Gemm &g, hipStream_t s) {
 
 hipError_t gemm(const Gemm &g, hipStream_t s) {
   if (g.M <= 0 || g.N <= 0 || g.K <= 0) return hipErrorInvalidValue;
+  if (g.colsum) return gemm_mfma_km_bf16(g, s);  // the only kernel with that by-product
   if (g.dtype == SSDT_BF16) {
     hipError_t e = gemm_mfma_km_bf16(g, s);  // operands taken as stored, also k-major ones
     if (e != hipErrorNotSupported) return e;

@@ -373,7 +373,7 @@ size_t gemm_scratch_bytes(int M, int N, int K, bool transA, bool transB, int dty
 
 
 hipError_t gemm_mfma_bf16(const Gemm &g, hipStream_t s) {
-  if (g.dtype != SSDT_BF16) return hipErrorNotSupported;
+  if (g.dtype != SSDT_BF16 || g.colsum) return hipErrorNotSupported;
   if (g.M % 128 || g.N % 128 || g.K % kBK) return hipErrorNotSupported;
   if (g.ldc % 4 || !al8(g.C) || (g.C2 && !al8(g.C2)) || (g.bias && !al8(g.bias)) || (g.aux && !al8(g.aux)) ||
       (g.resid && (!al8(g.resid) || g.ldr % 4)))
@@ -402,7 +402,7 @@ hipError_t gemm_mfma_bf16(const Gemm &g, hipStream_t s) {
   }
   if (!al16(A) || !al16(Bt) || lda % 8 || ldb % 8) return hipErrorNotSupported;
   NtP p{g.M, g.N, g.K, A, Bt, lda, ldb, g.ldc, g.ldr, (uint16_t *)g.C, (uint16_t *)g.C2, (const uint16_t *)g.bias,
-        (const uint16_t *)g.resid, (const uint16_t *)g.aux, g.act, 0, 0, 8, 0};
+        (const uint16_t *)g.resid, (const uint16_t *)g.aux, g.act, 0, 0, 8, nullptr, 0, 0};
   const bool epi16 = g.ldc % 8 == 0 && al16(g.C) && (!g.C2 || al16(g.C2)) && (!g.bias || al16(g.bias)) &&
                      (!g.aux || al16(g.aux)) && (!g.resid || (al16(g.resid) && g.ldr % 8 == 0));
   // the large-tile kernel addresses a tile's 256 rows with 32-bit byte offsets

@@ -65,7 +65,7 @@ __device__ __forceinline__ bf16x8_t frag_nt(const lds_char_t *at, unsigned off) 
 
 // W = wavefronts per workgroup: 8 (each 128 x 64 of the tile, two per SIMD) or 4 (each 128 x 128, one per SIMD with
 // the accumulators in the AGPRs: a third fewer LDS reads per MFMA, nobody to hide a stall behind).
-template <int EPI, bool AKM, bool BKM, int W>
+template <int EPI, bool AKM, bool BKM, int W, bool CS>
 __global__ __launch_bounds__(W * 64) void gemm_km256_k(NtP p) {
   constexpr int MB = 8, NB = W == 8 ? 4 : 8, NT = W * 64, LJ = 2048 / NT;
   extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
@@ -161,13 +161,15 @@ __global__ __launch_bounds__(W * 64) void gemm_km256_k(NtP p) {
   };
 // first half of the stage in buffer BUF: step 0 and the first block of step 1, then the barrier.  On entry Af[0..7]
 // and Bf[0][0..3] hold the fragments of step 0 and the reads of Bf[1][0..3] (step 1) have been issued.
-#define SSDT_KM_HEAD(BUF, MORE)                                                                            \
+#define SSDT_KM_HEAD(BUF, MORE, SUM)                                                                       \
   {                                                                                                        \
     _Pragma("unroll") for (int i = 0; i < MB; ++i) {                                                       \
       mfma_block(i, 0, 0, NB);                                                                             \
+      if (SUM && i == 0) sum_block(0);                                                                     \
       Af[i] = rdA(i, 1, BUF);                                                                              \
     }                                                                                                      \
     mfma_block(0, 1, 0, NB);                                                                               \
+    if (SUM) sum_block(1);                                                                                 \
     if (MORE) {                                                                                            \
       /* every LDS read of this stage has returned, this wavefront's part of the next stage has landed */  \
       asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");                                          \
@@ -237,16 +239,56 @@ __global__ __launch_bounds__(W * 64) void gemm_km256_k(NtP p) {
 #pragma unroll
   for (int j = 0; j < NB; ++j) Bf[1][j] = rdB(j, 1, 0);
   SSDT_FENCE;
-  SSDT_KM_HEAD(0, true);
-  for (int st = 0; st + 4 <= nk; st += 2) {
-    SSDT_KM_TAIL(0, true, true);
-    SSDT_KM_HEAD(1, true);
-    SSDT_KM_TAIL(1, true, true);
-    SSDT_KM_HEAD(0, true);
+// the whole K loop; SUM (literal): also the column sums of the second operand
+#define SSDT_KM_LOOP(SUM)                                                                                  \
+  {                                                                                                        \
+    SSDT_KM_HEAD(0, true, SUM);                                                                            \
+    for (int st = 0; st + 4 <= nk; st += 2) {                                                              \
+      SSDT_KM_TAIL(0, true, true);                                                                         \
+      SSDT_KM_HEAD(1, true, SUM);                                                                          \
+      SSDT_KM_TAIL(1, true, true);                                                                         \
+      SSDT_KM_HEAD(0, true, SUM);                                                                          \
+    }                                                                                                      \
+    SSDT_KM_TAIL(0, true, false);                                                                          \
+    SSDT_KM_HEAD(1, false, SUM);                                                                           \
+    SSDT_KM_TAIL(1, false, false);                                                                         \
   }
-  SSDT_KM_TAIL(0, true, false);
-  SSDT_KM_HEAD(1, false);
-  SSDT_KM_TAIL(1, false, false);
+  // Column sums of the second operand (the bias gradient when this is a weight-gradient product: sum over tokens of
+  // dY), as a by-product: a block of rows of ones is multiplied in, one more MFMA per fragment of the second operand,
+  // by the wavefronts of the first tile row that hold distinct fragments; every row of the result is the sum, and a
+  // fixed order of additions makes it reproducible.  The loop exists twice so that the others do not pay for the test.
+  if (CS && tile_m == 0 && wm == 0) {
+    f32x4_t accs[NB];
+#pragma unroll
+    for (int j = 0; j < NB; ++j) accs[j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    union { unsigned w[4]; bf16x8_t v; } ones;
+    ones.w[0] = ones.w[1] = ones.w[2] = ones.w[3] = 0x3F803F80u;  // 1.0 eight times
+    auto sum_block = [&](int set) {
+      SSDT_FENCE;
+#pragma unroll
+      for (int j = 0; j < NB; ++j) accs[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Bf[set][j], ones.v, accs[j], 0, 0, 0);
+      SSDT_FENCE;
+    };
+    SSDT_KM_LOOP(true);
+    if (lr == 0) {  // this lane: row 0 of each block, columns j*16 + lq*4 + 0..3
+#pragma unroll
+      for (int j = 0; j < NB; ++j) {
+        uint16_t *o = p.colsum + n0 + wn * NB * 16 + j * 16 + lq * 4;
+        float v[4] = {accs[j][0], accs[j][1], accs[j][2], accs[j][3]};
+        if (p.colsum_acc) {
+          float old[4];
+          unpack4(*(const uint2 *)o, old);
+#pragma unroll
+          for (int t = 0; t < 4; ++t) v[t] += old[t];
+        }
+        *(uint2 *)o = pack4(v);
+      }
+    }
+  } else {
+    auto sum_block = [&](int) {};
+    SSDT_KM_LOOP(false);
+  }
+#undef SSDT_KM_LOOP
 #undef SSDT_KM_HEAD
 #undef SSDT_KM_TAIL
 #undef SSDT_LD
@@ -279,26 +321,27 @@ __global__ __launch_bounds__(W * 64) void gemm_km256_k(NtP p) {
   }
 }
 
-int g_km_waves = 8;  // test hook: wavefronts per workgroup, 8 or 4
 int g_km_stagger = -100;  // test hook: stages between the K-loop starting points of neighbouring XCDs (-100 = by shape, -1 = K/8, -2 = K/16)
 
-template <int EPI, bool AKM, bool BKM, int W>
+template <int EPI, bool AKM, bool BKM, int W, bool CS>
 static hipError_t launch_km(const NtP &p, hipStream_t s) {
   constexpr size_t stg = (size_t)W * 64 * kEpiLd * 4, stages = (size_t)4 * kBuf, smem = stg > stages ? stg : stages;
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void *)gemm_km256_k<EPI, AKM, BKM, W>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    hipError_t e = hipFuncSetAttribute((const void *)gemm_km256_k<EPI, AKM, BKM, W, CS>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
   prof::Scope ps(prof::GEMM_MFMA_KM, 2.0 * p.M * p.N * p.K, 0, s);
-  hipLaunchKernelGGL((gemm_km256_k<EPI, AKM, BKM, W>), dim3(p.tiles_m * p.tiles_n), dim3(W * 64), smem, s, p);
+  hipLaunchKernelGGL((gemm_km256_k<EPI, AKM, BKM, W, CS>), dim3(p.tiles_m * p.tiles_n), dim3(W * 64), smem, s, p);
   return hipGetLastError();
 }
 
 template <bool AKM, bool BKM>
 static hipError_t launch_km_epi(int epi, const NtP &p, hipStream_t s) {
-#define SSDT_CASE(E) case E: return g_km_waves == 4 ? launch_km<E, AKM, BKM, 4>(p, s) : launch_km<E, AKM, BKM, 8>(p, s);
+// (W = 4, one wavefront of 128 x 128 per SIMD with the accumulators in the AGPRs, was measured too: within 1 % of
+// W = 8 on every shape of the layer, so only the latter is built.)
+#define SSDT_CASE(E) case E: return launch_km<E, AKM, BKM, 8, false>(p, s);
   switch (epi) {
     SSDT_CASE(EPI_NONE)
     SSDT_CASE(EPI_BIAS)
@@ -345,13 +388,20 @@ hipError_t gemm_mfma_km_bf16(const Gemm &g, hipStream_t s) {
   if (g.epi == EPI_BIAS_ACT && !g.C2) return hipErrorInvalidValue;
   if (g.epi == EPI_BIAS_RESID && !g.resid) return hipErrorInvalidValue;
   if (g.epi == EPI_ACTBWD && !g.aux) return hipErrorInvalidValue;
+  if (g.colsum && ((uintptr_t)g.colsum & 7)) return hipErrorNotSupported;
   // a k-major tile row is 512 contiguous bytes at column m0 / n0: the leading dimension must hold whole tiles
   if ((akm && g.lda < g.M) || (bkm && g.ldb < g.N)) return hipErrorInvalidValue;
   NtP p{g.M, g.N, g.K, (const uint16_t *)g.A, (const uint16_t *)g.B, g.lda, g.ldb, g.ldc, g.ldr, (uint16_t *)g.C,
         (uint16_t *)g.C2, (const uint16_t *)g.bias, (const uint16_t *)g.resid, (const uint16_t *)g.aux, g.act,
-        g.M / kTile, g.N / kTile, 8, 0};
+        g.M / kTile, g.N / kTile, 8, (uint16_t *)g.colsum, g.colsum_accumulate ? 1 : 0, 0};
   p.stagger = stagger_for(g.N, g.K);
   p.gm = g_force_waves > 0 ? g_force_waves : (p.tiles_m >= p.tiles_n ? 4 : 8);
+  if (g.colsum) {  // by-product of the weight-gradient form only
+    if (!(akm && bkm)) return hipErrorNotSupported;
+    if (g.epi == EPI_NONE) return launch_km<EPI_NONE, true, true, 8, true>(p, s);
+    if (g.epi == EPI_BIAS_RESID) return launch_km<EPI_BIAS_RESID, true, true, 8, true>(p, s);
+    return hipErrorNotSupported;
+  }
   if (akm && bkm) return launch_km_epi<true, true>(g.epi, p, s);
   if (bkm) return launch_km_epi<false, true>(g.epi, p, s);
   if (akm) return launch_km_epi<true, false>(g.epi, p, s);

@@ -406,29 +406,16 @@ ssdt_status layer_bwd_impl(ssdt_ctx *ctx, const ssdt_layer_desc *desc, const ssd
     g.resid = accum ? pend.dW : nullptr; g.ldr = pend.Nout; g.act = desc->act; g.dtype = dt;
     return k::gemm(g, st);
   };
-  Ev *side_done = nullptr;  // last work enqueued on the side stream that the caller's stream has not waited for yet
   auto wgrad = [&](const void *in, int Kin, const void *dY, int Nout, int rows, void *dW, void *db) -> hipError_t {
-    if (side_done) {
-      // whatever the side stream was still reading (the previous dY) may be overwritten from here on
-      ctx->be->wait(stream, side_done);
-      drop(ctx->be.get(), side_done);
-      side_done = nullptr;
-    }
-    if (side && k::gemm_km_fits(Kin, Nout, rows, true, false, dt)) {
-      // Both operands are read as stored (tokens x features, the contraction running over tokens): no copies.
-      // Only the bias gradient, a bandwidth-bound pass over dY, goes to the side stream, underneath the two
-      // matrix products; the caller's stream joins the side stream at the next weight gradient or at the end of
-      // the layer.
-      if (db) {
-        Ev *go = hold(ctx->be->record(stream, false));  // dY is ready
-        ctx->be->wait(side, go);
-        drop(ctx->be.get(), go);
-        hipError_t e0 = k::colsum(dY, Nout, db, bf.partial_side, rows, Nout, dt, accum, side);
-        if (e0 != hipSuccess) return e0;
-        side_done = hold(ctx->be->record(side, false));
-      }
-      return mm(Kin, Nout, rows, in, Kin, true, dY, Nout, false, dW, accum ? k::EPI_BIAS_RESID : k::EPI_NONE,
-                accum ? dW : nullptr, nullptr);
+    if (k::gemm_km_fits(Kin, Nout, rows, true, false, dt)) {
+      // Both operands are read as stored (tokens x features, the contraction running over tokens): no copies, and
+      // the bias gradient (the column sums of dY) falls out of the same kernel.
+      k::Gemm g;
+      g.M = Kin; g.N = Nout; g.K = rows; g.A = in; g.lda = Kin; g.transA = true; g.B = dY; g.ldb = Nout; g.transB = false;
+      g.C = dW; g.ldc = Nout; g.epi = accum ? k::EPI_BIAS_RESID : k::EPI_NONE; g.resid = accum ? dW : nullptr; g.ldr = Nout;
+      g.act = desc->act; g.dtype = dt; g.colsum = db; g.colsum_accumulate = accum;
+      hipError_t e0 = k::gemm_mfma_km_bf16(g, st);
+      if (e0 != hipErrorNotSupported) return e0;  // (an alignment it does not take: the general path below)
     }
     const long ld = k::nt_copy_ld(rows);  // leading dimension of the two transposed copies
     const size_t a_bytes = ((size_t)Kin * ld * 2 + 255) / 256 * 256, b_bytes = (size_t)Nout * ld * 2;
@@ -569,11 +556,6 @@ ssdt_status layer_bwd_impl(ssdt_ctx *ctx, const ssdt_layer_desc *desc, const ssd
     HIP_IF(wgrad_flush());
   }
   HIP_IF(wgrad_flush());
-  if (side_done) {  // the bias gradients computed on the side stream belong to this call's results
-    ctx->be->wait(stream, side_done);
-    drop(ctx->be.get(), side_done);
-    side_done = nullptr;
-  }
   return ctx->scope_end(scope, SSDT_BWD);
 #undef GET
 #undef HIP_IF

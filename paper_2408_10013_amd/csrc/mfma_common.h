@@ -19,6 +19,8 @@ struct NtP {
   uint16_t *C, *C2;
   const uint16_t *bias, *resid, *aux;
   int act, tiles_m, tiles_n, gm;
+  uint16_t *colsum;  // gemm_km256_k: if set, colsum[n] (+)= sum over k of the second operand (k, n), n = 0..N-1
+  int colsum_acc;    //               nonzero: added to what colsum holds
   int stagger;  // gemm_km256_k: the workgroups of XCD x start their K loop x * stagger stages in (0 = all at stage 0)
 };
 
