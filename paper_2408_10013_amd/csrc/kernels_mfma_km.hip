@@ -63,48 +63,84 @@ __device__ __forceinline__ bf16x8_t frag_nt(const lds_char_t *at, unsigned off) 
   return u.v;
 }
 
-// W = wavefronts per workgroup: 8 (each 128 x 64 of the tile, two per SIMD) or 4 (each 128 x 128, one per SIMD with
-// the accumulators in the AGPRs: a third fewer LDS reads per MFMA, nobody to hide a stall behind).
+// W = wavefronts per workgroup: 8, each 128 x 64 of the tile, two per SIMD.  (A form with 4, each 128 x 128 with the
+// accumulators in the AGPRs and the loads issued one by one between the MFMAs, a third fewer LDS reads per MFMA, ran
+// within 1 % of this one on every shape, alone and in the layer, in both generations of this kernel: not built.)
 template <int EPI, bool AKM, bool BKM, int W, bool CS>
 __global__ __launch_bounds__(W * 64) void gemm_km256_k(NtP p) {
-  constexpr int MB = 8, NB = W == 8 ? 4 : 8, NT = W * 64, LJ = 2048 / NT;
+  static_assert(W == 8, "two wavefronts per SIMD");
+  constexpr int MB = 8, NB = 4;
   extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
   const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), wm = W == 8 ? wave >> 2 : wave >> 1, wn = W == 8 ? wave & 3 : wave & 1;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), wm = wave >> 2, wn = wave & 3;
   int tile_m, tile_n;
   tile_of(p, blockIdx.x, &tile_m, &tile_n);
   const int m0 = tile_m * kTile, n0 = tile_n * kTile;
 
-  // ---- loader: thread t fills 16-byte LDS positions j*NT + t of each operand's buffer, j = 0..LJ-1 -------------
-  // K-contiguous operand: position = (row j*NT/8 + t/8, slot t%8), slot holds global chunk (t%8) ^ ((row >> 1) & 7)
-  // (NT/8 is a multiple of 16, so the key does not depend on j).
-  // k-major operand: position = (k-row j*NT/32 + t/32, 16-byte half t%2 of 32-byte unit (t%32)/2), which holds
-  // global unit ((t%32)/2) ^ key(k-row).
-  unsigned voa[LJ], vob[LJ];
+  // ---- loader -------------------------------------------------------------------------------------------------
+  // Only the second four wavefronts load, all of a stage in one burst right behind the barrier: 8 instructions of
+  // 16 bytes per lane for each operand.  The two wavefronts of a SIMD do not alternate: the one launched first gets
+  // the matrix pipe whenever it can use it, so it runs through its stage and then waits at the barrier while the
+  // other catches up (cycle stamps: about 1100 of a stage's 2800 cycles at the barrier for wavefronts 0-3, under 100
+  // for 4-7).  A load instruction occupies the address unit of the compute unit for 16 cycles, and a wavefront that
+  // cannot hand over a load cannot issue the MFMAs behind it either, so loads belong to the wavefronts that are
+  // waiting for the pipe anyway, and the ones that own the pipe have none.
+  // Loader thread t (0..255) and instruction j fill, per operand,
+  //   K-contiguous: 16-byte position j*256 + t = (row j*32 + t/8, slot t%8), slot holds global chunk (t%8) ^ ((row >> 1) & 7);
+  //   k-major: k-row 16*(j/2) + 4*(j%2) + (t/32)%4 + 8*(t/128), 16-byte half t%2 of 32-byte unit (t%32)/2, which holds
+  //            global unit ((t%32)/2) ^ key(k-row); rows are dealt so that the key is t/32 whatever j is, and the two
+  //            rows of a wavefront are neighbours (its 1 KiB of LDS is contiguous).
+  const bool loader = wave >= 4;
+  const int lt = tid - 256, lw = wave - 4;  // loader thread / wavefront index (meaningful if loader)
+  unsigned voa, vob, lda_dst, ldb_dst;                    // per-lane global byte offset; this wavefront's LDS offset
   {
-    const int lrow = tid >> 3, lchunk = (tid & 7) ^ ((lrow >> 1) & 7);
-    const int c = tid & 31;
-#pragma unroll
-    for (int j = 0; j < LJ; ++j) {
-      const int kr = j * (NT / 32) + (tid >> 5), key = (kr & 3) | (((kr >> 3) & 1) << 2), unit = (c >> 1) ^ key;
-      voa[j] = AKM ? (unsigned)(kr * (int)p.lda) * 2u + unit * 32 + (c & 1) * 16
-                   : (unsigned)((lrow + j * (NT / 8)) * (int)p.lda + lchunk * 8) * 2u;
-      vob[j] = BKM ? (unsigned)(kr * (int)p.ldb) * 2u + unit * 32 + (c & 1) * 16
-                   : (unsigned)((lrow + j * (NT / 8)) * (int)p.ldb + lchunk * 8) * 2u;
-    }
+    const int lrow = lt >> 3, lchunk = (lt & 7) ^ ((lrow >> 1) & 7);
+    const int c = lt & 31, b = lt >> 5, key = b, kr = (b & 3) + 8 * (b >> 2);
+    const unsigned km_dst = (unsigned)(2 * (lw & 1) + 8 * (lw >> 1)) * 512, nt_dst = (unsigned)lw * 1024;
+    voa = AKM ? (unsigned)(kr * (int)p.lda) * 2u + ((c >> 1) ^ key) * 32 + (c & 1) * 16 : (unsigned)(lrow * (int)p.lda + lchunk * 8) * 2u;
+    vob = BKM ? (unsigned)(kr * (int)p.ldb) * 2u + ((c >> 1) ^ key) * 32 + (c & 1) * 16 : (unsigned)(lrow * (int)p.ldb + lchunk * 8) * 2u;
+    lda_dst = AKM ? km_dst : nt_dst;
+    ldb_dst = BKM ? km_dst : nt_dst;
   }
   const char *pa = (const char *)(AKM ? p.A + m0 : p.A + (long)m0 * p.lda);    // stage 0 of the tile
   const char *pb = (const char *)(BKM ? p.Bt + n0 : p.Bt + (long)n0 * p.ldb);
   const long sa = AKM ? (long)kStageK * p.lda * 2 : kStageK * 2, sb = BKM ? (long)kStageK * p.ldb * 2 : kStageK * 2;
+  // global byte offset from instruction j to j + 1, j even / odd: 32 rows (K-contiguous), or 4 / 12 k-rows (k-major: the
+  // instructions start at k-rows 0, 4, 16, 20, 32, ...); the same in LDS bytes
+  const unsigned ga0 = (unsigned)((AKM ? 4 : 32) * p.lda * 2), ga1 = (unsigned)((AKM ? 12 : 32) * p.lda * 2);
+  const unsigned gb0 = (unsigned)((BKM ? 4 : 32) * p.ldb * 2), gb1 = (unsigned)((BKM ? 12 : 32) * p.ldb * 2);
+  constexpr unsigned la0 = AKM ? 4 * 512 : 4096, la1 = AKM ? 12 * 512 : 4096, lb0 = BKM ? 4 * 512 : 4096, lb1 = BKM ? 12 * 512 : 4096;
   const unsigned lds0 = (unsigned)(uintptr_t)smem;
-  const unsigned wbase = lds0 + wave * 1024;  // this wavefront's 1 KiB of every 8 KiB a load instruction fills
-// one 16-byte-per-lane direct-to-LDS load: M0 = LDS address of the wavefront's 1 KiB, global address = scalar base +
-// per-lane byte offset (no instruction offset: it would be added to the LDS address too)
-#define SSDT_LD(PTR, VOFF, LDSOFF)                                                                         \
-  asm volatile("s_add_u32 m0, %0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"                         \
-               :: "s"(wbase), "v"(VOFF), "s"(PTR), "n"(LDSOFF) : "memory", "scc")
-#define SSDT_LDA(BUF, PTR, j) SSDT_LD(PTR, voa[j], (BUF) * kBuf + (j) * NT * 16)
-#define SSDT_LDB(BUF, PTR, j) SSDT_LD(PTR, vob[j], kLdsB + (BUF) * kBuf + (j) * NT * 16)
+  const unsigned wa = lds0 + lda_dst, wb = lds0 + kLdsB + ldb_dst;
+  const int is_loader = __builtin_amdgcn_readfirstlane(loader ? 1 : 0);
+// One instruction pair (A, B) of the burst: 16 bytes per lane straight to LDS, M0 = LDS address of the wavefront's
+// 1 KiB, global address = scalar base + per-lane byte offset (no instruction offset: it would be added to the LDS
+// address too).  The scalar add between the write of M0 and the load is the wait state that pair needs; the per-lane
+// offset moves on to the next instruction's rows behind the load (an address register is read when the load issues).
+#define SSDT_LD2(LA, LB, GA, GB)                                                                           \
+  "s_mov_b32 m0, %[ta]\n\ts_add_u32 %[ta], %[ta], %[" #LA "]\n\tglobal_load_lds_dwordx4 %[va], %[pa]\n\t"     \
+  "v_add_u32 %[va], %[" #GA "], %[va]\n\t"                                                                \
+  "s_mov_b32 m0, %[tb]\n\ts_add_u32 %[tb], %[tb], %[" #LB "]\n\tglobal_load_lds_dwordx4 %[vb], %[pb]\n\t"     \
+  "v_add_u32 %[vb], %[" #GB "], %[vb]\n\t"
+// The whole stage at pa / pb into buffer BUF, by the loading wavefronts only.  One statement with its own branch: a
+// branch the compiler knows of splits the hand-scheduled loop into blocks, and the register allocation that comes out
+// of that spills fragments.
+#define SSDT_LOAD_STAGE(BUF)                                                                               \
+  {                                                                                                        \
+    unsigned ta_, tb_, va_, vb_;                                                                           \
+    asm volatile("s_cmp_eq_u32 %[ld], 0\n\ts_cbranch_scc1 .Lssdt_noload_%=\n\t"                            \
+                 "s_add_u32 %[ta], %[wa], %[ba]\n\ts_add_u32 %[tb], %[wb], %[bb]\n\t"                       \
+                 "v_mov_b32 %[va], %[voa]\n\tv_mov_b32 %[vb], %[vob]\n\t"                                   \
+                 SSDT_LD2(la0, lb0, ga0, gb0) SSDT_LD2(la1, lb1, ga1, gb1) SSDT_LD2(la0, lb0, ga0, gb0)      \
+                 SSDT_LD2(la1, lb1, ga1, gb1) SSDT_LD2(la0, lb0, ga0, gb0) SSDT_LD2(la1, lb1, ga1, gb1)      \
+                 SSDT_LD2(la0, lb0, ga0, gb0) SSDT_LD2(la1, lb1, ga1, gb1)                                   \
+                 ".Lssdt_noload_%=:"                                                                       \
+                 : [ta] "=&s"(ta_), [tb] "=&s"(tb_), [va] "=&v"(va_), [vb] "=&v"(vb_)                      \
+                 : [ld] "s"(is_loader), [wa] "s"(wa), [wb] "s"(wb), [ba] "n"((BUF) * kBuf), [bb] "n"((BUF) * kBuf), \
+                   [pa] "s"(pa), [pb] "s"(pb), [voa] "v"(voa), [vob] "v"(vob), [ga0] "s"(ga0), [ga1] "s"(ga1), \
+                   [gb0] "s"(gb0), [gb1] "s"(gb1), [la0] "n"(la0), [la1] "n"(la1), [lb0] "n"(lb0), [lb1] "n"(lb1) \
+                 : "memory", "scc");                                                                       \
+  }
 
   // ---- fragment addresses ---------------------------------------------------------------------------------
   const int lr = lane & 15, lq = lane >> 4;
@@ -149,22 +185,29 @@ __global__ __launch_bounds__(W * 64) void gemm_km256_k(NtP p) {
   // block as soon as a block's MFMAs have been issued; the B fragments in two sets that alternate per step.  All reads
   // of a stage have been issued by the end of its first step, so the stage's one barrier sits behind the first block
   // of the second step: after it the other buffer (the next stage, whose loads were waited for just before) may be
-  // read, and the stage after next is loaded over this one, two loads behind the first MFMAs of each of the next four
-  // blocks.  The code is written as the two halves either side of that barrier, and the loop is cut there, where no
-  // LDS read is outstanding (with the cut at the stage boundary the compiler, which does not carry its count of
-  // outstanding reads around a loop, waited for all of them at the head of every iteration).
+  // read, and the loading wavefronts bring the stage after next in over this one.  The code is written as the two
+  // halves either side of that barrier, and the loop is cut there, where no LDS read is outstanding (with the cut at
+  // the stage boundary the compiler, which does not carry its count of outstanding reads around a loop, waited for
+  // all of them at the head of every iteration).
   auto mfma_block = [&](int i, int set, int j0, int j1) {
     SSDT_FENCE;
 #pragma unroll
     for (int j = j0; j < j1; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Bf[set][j], Af[i], acc[i][j], 0, 0, 0);
     SSDT_FENCE;
   };
-// first half of the stage in buffer BUF: step 0 and the first block of step 1, then the barrier.  On entry Af[0..7]
-// and Bf[0][0..3] hold the fragments of step 0 and the reads of Bf[1][0..3] (step 1) have been issued.
+// LDS reads are never issued back to back: the command queue of the LDS takes a few, and a wavefront that cannot
+// hand over a read cannot issue the MFMAs behind it either.  With the five reads that used to follow the barrier in
+// one group, and the four at the end of the stage, that queue was full in 18 % of all cycles (SQ_LDS_CMD_FIFO_FULL
+// against SQ_BUSY_CYCLES; 0.6 % now).  Every read below has at least one MFMA of its own wavefront in front of it.
+// First half of the stage in buffer BUF: step 0 and the first block of step 1, then the barrier.  On entry Af[0..7]
+// and Bf[0][0..3] hold (or are about to receive) the fragments of step 0; the B fragments of step 1 are read here,
+// one in each of the first four blocks, the A fragments of step 1 block by block behind their last use.
 #define SSDT_KM_HEAD(BUF, MORE, SUM)                                                                       \
   {                                                                                                        \
     _Pragma("unroll") for (int i = 0; i < MB; ++i) {                                                       \
-      mfma_block(i, 0, 0, NB);                                                                             \
+      mfma_block(i, 0, 0, 2);                                                                              \
+      if (i < NB) Bf[1][i] = rdB(i, 1, BUF);                                                               \
+      mfma_block(i, 0, 2, NB);                                                                             \
       if (SUM && i == 0) sum_block(0);                                                                     \
       Af[i] = rdA(i, 1, BUF);                                                                              \
     }                                                                                                      \
@@ -178,34 +221,23 @@ __global__ __launch_bounds__(W * 64) void gemm_km256_k(NtP p) {
       SSDT_FENCE;                                                                                          \
     }                                                                                                      \
   }
-// second half: the rest of step 1 out of the registers, while the next stage (buffer BUF ^ 1) is read and the stage
-// after next is loaded into buffer BUF.  MORE / MORE2: a next stage / a stage after next exists.
+// Second half: the loads of the stage after next into buffer BUF, then the rest of step 1 out of the registers
+// while step 0 of the next stage (buffer BUF ^ 1) is read: its B fragments and the first A fragment inside the first
+// blocks, the other A fragments block by block.  MORE / MORE2: a next stage / a stage after next exists.
 #define SSDT_KM_TAIL(BUF, MORE, MORE2)                                                                     \
   {                                                                                                        \
-    if (MORE) {                                                                                            \
-      _Pragma("unroll") for (int j = 0; j < NB; ++j) Bf[0][j] = rdB(j, 0, (BUF) ^ 1);                      \
-      Af[0] = rdA(0, 0, (BUF) ^ 1);                                                                        \
+    if (MORE2) {                                                                                           \
+      SSDT_FENCE;                                                                                          \
+      SSDT_LOAD_STAGE(BUF);                                                                                \
+      SSDT_FENCE;                                                                                          \
     }                                                                                                      \
     _Pragma("unroll") for (int i = 1; i < MB; ++i) {                                                       \
       mfma_block(i, 1, 0, 1);                                                                              \
-      if (MORE2 && i <= LJ) SSDT_LDA(BUF, pa, i - 1);                                                      \
-      mfma_block(i, 1, 1, 2);                                                                              \
-      if (MORE2 && i <= LJ) SSDT_LDB(BUF, pb, i - 1);                                                      \
-      if (LJ == MB && i == MB - 1) { /* eight loads per operand over seven blocks: the last block takes two */ \
-        mfma_block(i, 1, 2, 3);                                                                            \
-        if (MORE2) SSDT_LDA(BUF, pa, LJ - 1);                                                              \
-        mfma_block(i, 1, 3, 4);                                                                            \
-        if (MORE2) SSDT_LDB(BUF, pb, LJ - 1);                                                              \
-        mfma_block(i, 1, 4, NB);                                                                           \
-      } else {                                                                                             \
-        mfma_block(i, 1, 2, NB);                                                                           \
-      }                                                                                                    \
+      if (MORE && i <= NB) Bf[0][i - 1] = rdB(i - 1, 0, (BUF) ^ 1);                                        \
+      mfma_block(i, 1, 1, 3);                                                                              \
+      if (MORE && i == 1) Af[0] = rdA(0, 0, (BUF) ^ 1);                                                    \
+      mfma_block(i, 1, 3, NB);                                                                             \
       if (MORE) Af[i] = rdA(i, 0, (BUF) ^ 1);                                                              \
-    }                                                                                                      \
-    if (MORE) {                                                                                            \
-      SSDT_FENCE;                                                                                          \
-      _Pragma("unroll") for (int j = 0; j < NB; ++j) Bf[1][j] = rdB(j, 1, (BUF) ^ 1);                      \
-      SSDT_FENCE;                                                                                          \
     }                                                                                                      \
     pa += sa; pb += sb;                                                                                    \
     if (++cur == nk) { cur = 0; pa -= wrap_a; pb -= wrap_b; }                                              \
@@ -218,17 +250,14 @@ __global__ __launch_bounds__(W * 64) void gemm_km256_k(NtP p) {
   const long wrap_a = (long)nk * sa, wrap_b = (long)nk * sb;
   pa += (long)s0 * sa; pb += (long)s0 * sb;
   int cur = s0;
-#pragma unroll
-  for (int j = 0; j < LJ; ++j) { SSDT_LDA(0, pa, j); SSDT_LDB(0, pb, j); }
+  SSDT_LOAD_STAGE(0);
   pa += sa; pb += sb;
   if (++cur == nk) { cur = 0; pa -= wrap_a; pb -= wrap_b; }
-#pragma unroll
-  for (int j = 0; j < LJ; ++j) { SSDT_LDA(1, pa, j); SSDT_LDB(1, pb, j); }
+  SSDT_LOAD_STAGE(1);
   pa += sa; pb += sb;  // from here on: the stage after next
   if (++cur == nk) { cur = 0; pa -= wrap_a; pb -= wrap_b; }
-  // stage 0 has landed (stage 1, this thread's last 2 * LJ loads, may still be on its way)
-  if (LJ == 4) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-  else asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+  // stage 0 has landed (stage 1, a loader's last 16 loads, may still be on its way)
+  asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
   SSDT_FENCE;
@@ -236,8 +265,6 @@ __global__ __launch_bounds__(W * 64) void gemm_km256_k(NtP p) {
   for (int j = 0; j < NB; ++j) Bf[0][j] = rdB(j, 0, 0);
 #pragma unroll
   for (int i = 0; i < MB; ++i) Af[i] = rdA(i, 0, 0);
-#pragma unroll
-  for (int j = 0; j < NB; ++j) Bf[1][j] = rdB(j, 1, 0);
   SSDT_FENCE;
 // the whole K loop; SUM (literal): also the column sums of the second operand
 #define SSDT_KM_LOOP(SUM)                                                                                  \
@@ -291,9 +318,8 @@ __global__ __launch_bounds__(W * 64) void gemm_km256_k(NtP p) {
 #undef SSDT_KM_LOOP
 #undef SSDT_KM_HEAD
 #undef SSDT_KM_TAIL
-#undef SSDT_LD
-#undef SSDT_LDA
-#undef SSDT_LDB
+#undef SSDT_LOAD_STAGE
+#undef SSDT_LD2
 
   // epilogue through LDS (free now), 64x64 sub-tiles of the wavefront's part, one column of sub-tiles at a time:
   // lane l of block (i, j) holds row i*16 + (l & 15), columns j*16 + (l >> 4)*4 + 0..3
