@@ -66,7 +66,7 @@ __device__ __forceinline__ bf16x8_t frag_nt(const lds_char_t *at, unsigned off) 
 // W = wavefronts per workgroup: 8, each 128 x 64 of the tile, two per SIMD.  (A form with 4, each 128 x 128 with the
 // accumulators in the AGPRs and the loads issued one by one between the MFMAs, a third fewer LDS reads per MFMA, ran
 // within 1 % of this one on every shape, alone and in the layer, in both generations of this kernel: not built.)
-template <int EPI, bool AKM, bool BKM, int W, bool CS>
+template <int EPI, bool AKM, bool BKM, int W, bool CS, bool PF>
 __global__ __launch_bounds__(W * 64) void gemm_km256_k(NtP p) {
   static_assert(W == 8, "two wavefronts per SIMD");
   constexpr int MB = 8, NB = 4;
@@ -112,7 +112,32 @@ __global__ __launch_bounds__(W * 64) void gemm_km256_k(NtP p) {
   constexpr unsigned la0 = AKM ? 4 * 512 : 4096, la1 = AKM ? 12 * 512 : 4096, lb0 = BKM ? 4 * 512 : 4096, lb1 = BKM ? 12 * 512 : 4096;
   const unsigned lds0 = (unsigned)(uintptr_t)smem;
   const unsigned wa = lds0 + lda_dst, wb = lds0 + kLdsB + ldb_dst;
-  const int is_loader = __builtin_amdgcn_readfirstlane(loader ? 1 : 0);
+  const int nk = p.K / kStageK;  // even, >= 2 (checked by the launcher)
+  const long wrap_a = (long)nk * sa, wrap_b = (long)nk * sb;
+  int cur = 0, left = 0;         // stage at pa / pb; stages the loop still loads after that one
+  const int is_loader = wave >> 2;  // (plain scalar arithmetic: a select here may end up in a vector register)
+  // L2 prefetch (instantiations with PF; p.pf > 0: stages ahead).  The 32 workgroups that an XCD runs side by side (p.gm tile rows x 32 / p.gm
+  // tile columns) share 12 operand panels; whoever asks first for a line of a stage waits for memory, a fifth of all
+  // requests.  With p.pf every loading wavefront ends its burst with one more load, 4 bytes per lane into a dump area
+  // of LDS, at lines of the stage p.pf stages further on: wavefronts 4 and 5 a half each of this workgroup's share of
+  // its A panel (1 / sharers of the panel), 6 and 7 the same of its B panel, 96 lines per workgroup and stage, so that
+  // the XCD's workgroups together touch every line once (lanes beyond the share repeat addresses).  Loads return in
+  // order, so the wait before the barrier can leave this last one outstanding: it has two stages to come back.  The
+  // sharing pattern only decides which lines are touched early: every address lies inside this workgroup's own panels
+  // and K range whatever the grid looks like (past the end of the K loop the touch stays on the stage being loaded).
+  const int pfd = PF ? p.pf : 0;
+  const bool pt_is_a = lw < 2;
+  unsigned vot = 0;
+  if (PF) {
+    const int gm = p.gm, nsa = 32 / gm;
+    const int per = pt_is_a ? kTile / nsa : kTile / gm, nl = per / 2;
+    const int line = (pt_is_a ? tile_n % nsa : tile_m % gm) * per + (lw & 1) * nl + lane % nl;
+    const bool km = pt_is_a ? AKM : BKM;
+    const int ld = (int)(pt_is_a ? p.lda : p.ldb);
+    vot = km ? (unsigned)((line >> 2) * ld) * 2u + (line & 3) * 128 : (unsigned)(line * ld) * 2u;
+  }
+  const unsigned wdump = lds0 + 4 * kBuf + wave * 256;  // 256 bytes per wavefront behind the stage buffers
+  const long dsa = (long)pfd * sa, dsb = (long)pfd * sb;
 // One instruction pair (A, B) of the burst: 16 bytes per lane straight to LDS, M0 = LDS address of the wavefront's
 // 1 KiB, global address = scalar base + per-lane byte offset (no instruction offset: it would be added to the LDS
 // address too).  The scalar add between the write of M0 and the load is the wait state that pair needs; the per-lane
@@ -125,21 +150,33 @@ __global__ __launch_bounds__(W * 64) void gemm_km256_k(NtP p) {
 // The whole stage at pa / pb into buffer BUF, by the loading wavefronts only.  One statement with its own branch: a
 // branch the compiler knows of splits the hand-scheduled loop into blocks, and the register allocation that comes out
 // of that spills fragments.
-#define SSDT_LOAD_STAGE(BUF)                                                                               \
-  {                                                                                                        \
-    unsigned ta_, tb_, va_, vb_;                                                                           \
+#define SSDT_LOAD_STAGE_ASM(BUF, TOUCH, ...)                                                               \
     asm volatile("s_cmp_eq_u32 %[ld], 0\n\ts_cbranch_scc1 .Lssdt_noload_%=\n\t"                            \
                  "s_add_u32 %[ta], %[wa], %[ba]\n\ts_add_u32 %[tb], %[wb], %[bb]\n\t"                       \
                  "v_mov_b32 %[va], %[voa]\n\tv_mov_b32 %[vb], %[vob]\n\t"                                   \
                  SSDT_LD2(la0, lb0, ga0, gb0) SSDT_LD2(la1, lb1, ga1, gb1) SSDT_LD2(la0, lb0, ga0, gb0)      \
                  SSDT_LD2(la1, lb1, ga1, gb1) SSDT_LD2(la0, lb0, ga0, gb0) SSDT_LD2(la1, lb1, ga1, gb1)      \
                  SSDT_LD2(la0, lb0, ga0, gb0) SSDT_LD2(la1, lb1, ga1, gb1)                                   \
+                 TOUCH                                                                                     \
                  ".Lssdt_noload_%=:"                                                                       \
                  : [ta] "=&s"(ta_), [tb] "=&s"(tb_), [va] "=&v"(va_), [vb] "=&v"(vb_)                      \
                  : [ld] "s"(is_loader), [wa] "s"(wa), [wb] "s"(wb), [ba] "n"((BUF) * kBuf), [bb] "n"((BUF) * kBuf), \
                    [pa] "s"(pa), [pb] "s"(pb), [voa] "v"(voa), [vob] "v"(vob), [ga0] "s"(ga0), [ga1] "s"(ga1), \
                    [gb0] "s"(gb0), [gb1] "s"(gb1), [la0] "n"(la0), [la1] "n"(la1), [lb0] "n"(lb0), [lb1] "n"(lb1) \
-                 : "memory", "scc");                                                                       \
+                   __VA_ARGS__                                                                             \
+                 : "memory", "scc")
+#define SSDT_LOAD_STAGE(BUF)                                                                               \
+  {                                                                                                        \
+    unsigned ta_, tb_, va_, vb_;                                                                           \
+    if constexpr (PF) {                                                                                    \
+      /* the touched stage: p.pf on from the one at pa / pb if the loop gets that far, else that one */    \
+      const bool far_ = left >= pfd, wr_ = cur + pfd >= nk;                                                 \
+      const char *pt_ = pt_is_a ? pa + (far_ ? dsa - (wr_ ? wrap_a : 0) : 0) : pb + (far_ ? dsb - (wr_ ? wrap_b : 0) : 0); \
+      SSDT_LOAD_STAGE_ASM(BUF, "s_mov_b32 m0, %[dump]\n\ts_nop 0\n\tglobal_load_lds_dword %[vot], %[pt]\n\t",   \
+                          , [dump] "s"(wdump), [vot] "v"(vot), [pt] "s"(pt_));                             \
+    } else {                                                                                               \
+      SSDT_LOAD_STAGE_ASM(BUF, "", );                                                                      \
+    }                                                                                                      \
   }
 
   // ---- fragment addresses ---------------------------------------------------------------------------------
@@ -202,6 +239,12 @@ __global__ __launch_bounds__(W * 64) void gemm_km256_k(NtP p) {
 // First half of the stage in buffer BUF: step 0 and the first block of step 1, then the barrier.  On entry Af[0..7]
 // and Bf[0][0..3] hold (or are about to receive) the fragments of step 0; the B fragments of step 1 are read here,
 // one in each of the first four blocks, the A fragments of step 1 block by block behind their last use.
+// waits for every LDS read and for all loads but the last N (N = WITH in the instantiations with touches, else WITHOUT)
+#define SSDT_WAIT_LOADS(WITH, WITHOUT)                                                                     \
+  {                                                                                                        \
+    if constexpr (PF) asm volatile("s_waitcnt vmcnt(" WITH ") lgkmcnt(0)" ::: "memory");                   \
+    else asm volatile("s_waitcnt vmcnt(" WITHOUT ") lgkmcnt(0)" ::: "memory");                             \
+  }
 #define SSDT_KM_HEAD(BUF, MORE, SUM)                                                                       \
   {                                                                                                        \
     _Pragma("unroll") for (int i = 0; i < MB; ++i) {                                                       \
@@ -215,7 +258,7 @@ __global__ __launch_bounds__(W * 64) void gemm_km256_k(NtP p) {
     if (SUM) sum_block(1);                                                                                 \
     if (MORE) {                                                                                            \
       /* every LDS read of this stage has returned, this wavefront's part of the next stage has landed */  \
-      asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");                                          \
+      SSDT_WAIT_LOADS("1", "0");                                                                           \
       __builtin_amdgcn_s_barrier();                                                                        \
       asm volatile("" ::: "memory");                                                                       \
       SSDT_FENCE;                                                                                          \
@@ -239,25 +282,23 @@ __global__ __launch_bounds__(W * 64) void gemm_km256_k(NtP p) {
       mfma_block(i, 1, 3, NB);                                                                             \
       if (MORE) Af[i] = rdA(i, 0, (BUF) ^ 1);                                                              \
     }                                                                                                      \
-    pa += sa; pb += sb;                                                                                    \
+    pa += sa; pb += sb; --left;                                                                            \
     if (++cur == nk) { cur = 0; pa -= wrap_a; pb -= wrap_b; }                                              \
   }
 
-  const int nk = p.K / kStageK;  // even, >= 2 (checked by the launcher)
   // The K loop may start at a stage other than 0 and wrap around (every workgroup of an XCD at the same stage, so
   // that they still share their panels in the L2; the XCDs apart from each other).
   const int s0 = __builtin_amdgcn_readfirstlane((int)((blockIdx.x & 7) * p.stagger) % nk) & ~1;
-  const long wrap_a = (long)nk * sa, wrap_b = (long)nk * sb;
   pa += (long)s0 * sa; pb += (long)s0 * sb;
-  int cur = s0;
+  cur = s0; left = nk - 1;
   SSDT_LOAD_STAGE(0);
-  pa += sa; pb += sb;
+  pa += sa; pb += sb; --left;
   if (++cur == nk) { cur = 0; pa -= wrap_a; pb -= wrap_b; }
   SSDT_LOAD_STAGE(1);
-  pa += sa; pb += sb;  // from here on: the stage after next
+  pa += sa; pb += sb; --left;  // from here on: the stage after next
   if (++cur == nk) { cur = 0; pa -= wrap_a; pb -= wrap_b; }
-  // stage 0 has landed (stage 1, a loader's last 16 loads, may still be on its way)
-  asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+  // stage 0 has landed (stage 1, a loader's last 16 loads, and the two touches may still be on their way)
+  SSDT_WAIT_LOADS("18", "16");
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
   SSDT_FENCE;
@@ -319,11 +360,13 @@ __global__ __launch_bounds__(W * 64) void gemm_km256_k(NtP p) {
 #undef SSDT_KM_HEAD
 #undef SSDT_KM_TAIL
 #undef SSDT_LOAD_STAGE
+#undef SSDT_LOAD_STAGE_ASM
+#undef SSDT_WAIT_LOADS
 #undef SSDT_LD2
 
   // epilogue through LDS (free now), 64x64 sub-tiles of the wavefront's part, one column of sub-tiles at a time:
   // lane l of block (i, j) holds row i*16 + (l & 15), columns j*16 + (l >> 4)*4 + 0..3
-  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");  // (vmcnt: the last touch, whose dump area the staging area covers)
   __builtin_amdgcn_s_barrier();  // every wavefront has finished reading the last stage
   asm volatile("" ::: "memory");
   float *stg = (float *)smem + wave * (64 * kEpiLd);
@@ -349,18 +392,27 @@ __global__ __launch_bounds__(W * 64) void gemm_km256_k(NtP p) {
 
 int g_km_stagger = -100;  // test hook: stages between the K-loop starting points of neighbouring XCDs (-100 = by shape, -1 = K/8, -2 = K/16)
 
-template <int EPI, bool AKM, bool BKM, int W, bool CS>
-static hipError_t launch_km(const NtP &p, hipStream_t s) {
+template <int EPI, bool AKM, bool BKM, int W, bool CS, bool PF>
+static hipError_t launch_km_pf(const NtP &p, hipStream_t s) {
   constexpr size_t stg = (size_t)W * 64 * kEpiLd * 4, stages = (size_t)4 * kBuf, smem = stg > stages ? stg : stages;
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void *)gemm_km256_k<EPI, AKM, BKM, W, CS>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    hipError_t e = hipFuncSetAttribute((const void *)gemm_km256_k<EPI, AKM, BKM, W, CS, PF>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
   prof::Scope ps(prof::GEMM_MFMA_KM, 2.0 * p.M * p.N * p.K, 0, s);
-  hipLaunchKernelGGL((gemm_km256_k<EPI, AKM, BKM, W, CS>), dim3(p.tiles_m * p.tiles_n), dim3(W * 64), smem, s, p);
+  hipLaunchKernelGGL((gemm_km256_k<EPI, AKM, BKM, W, CS, PF>), dim3(p.tiles_m * p.tiles_n), dim3(W * 64), smem, s, p);
   return hipGetLastError();
+}
+
+// the prefetching instantiation exists for the forms whose first operand is K-contiguous (prefetch_for)
+template <int EPI, bool AKM, bool BKM, int W, bool CS>
+static hipError_t launch_km(const NtP &p, hipStream_t s) {
+  if constexpr (!AKM && !CS) {
+    if (p.pf > 0) return launch_km_pf<EPI, AKM, BKM, W, CS, true>(p, s);
+  }
+  return launch_km_pf<EPI, AKM, BKM, W, CS, false>(p, s);
 }
 
 template <bool AKM, bool BKM>
@@ -379,6 +431,7 @@ static hipError_t launch_km_epi(int epi, const NtP &p, hipStream_t s) {
   return hipErrorInvalidValue;
 }
 
+int g_km_pf = -1;   // test hook: stages that the L2 prefetch runs ahead of the loads (-1 = by shape, 0 = none)
 int g_km_mode = 1;  // test hook: 0 = never use this kernel, 1 = for k-major operands, 2 = also for the NT form
 
 // Shape part of the conditions below: what a caller can know before it has pointers (workspace sizing, the choice
@@ -392,12 +445,22 @@ static int stagger_for(int N, int K) {
   return (nk <= 128 && N / kTile >= 64) ? nk / 8 : 0;
 }
 
+// L2 prefetch distance by shape (0 = none).  It pays where the first operand is K-contiguous with rows far apart, i.e.
+// a long K (sustained, alone: 32768 x 8192 x 32768 K-contiguous +6 %, x 24576 +8 %, the forward product with K = 32768
+// +4 %), costs 2 % at K = 8192 (the touches take the address unit's time and there is less latency to hide), and is
+// a wash on the weight gradients, both of whose operands are k-major (-0.4 to +2 %).
+static int prefetch_for(int K, bool akm, bool bkm) {
+  (void)bkm;
+  if (g_km_pf >= 0) return g_km_pf;
+  return (!akm && K >= 16384) ? 2 : 0;
+}
+
 bool gemm_km_fits(int M, int N, int K, bool transA, bool transB, int dtype) {
   if (dtype != SSDT_BF16 || g_km_mode == 0) return false;
   if (M % kTile || N % kTile || K % (2 * kStageK) || K < 2 * kStageK) return false;
   if ((long)(M / kTile) * (N / kTile) < 256) return false;
-  // the K-contiguous form stays with gemm_nt256_k unless this kernel's staggered K loop pays for the shape
-  if (!transA && transB && g_km_mode < 2 && stagger_for(N, K) == 0) return false;
+  // the K-contiguous form stays with gemm_nt256_k unless this kernel's staggered K loop or its prefetch pays for the shape
+  if (!transA && transB && g_km_mode < 2 && stagger_for(N, K) == 0 && prefetch_for(K, false, false) == 0) return false;
   return true;
 }
 
@@ -422,6 +485,7 @@ hipError_t gemm_mfma_km_bf16(const Gemm &g, hipStream_t s) {
         g.M / kTile, g.N / kTile, 8, (uint16_t *)g.colsum, g.colsum_accumulate ? 1 : 0, 0};
   p.stagger = stagger_for(g.N, g.K);
   p.gm = g_force_waves > 0 ? g_force_waves : (p.tiles_m >= p.tiles_n ? 4 : 8);
+  p.pf = (!akm && !g.colsum && (p.gm & (p.gm - 1)) == 0 && p.gm <= 32) ? prefetch_for(g.K, akm, bkm) : 0;
   if (g.colsum) {  // by-product of the weight-gradient form only
     if (!(akm && bkm)) return hipErrorNotSupported;
     if (g.epi == EPI_NONE) return launch_km<EPI_NONE, true, true, 8, true>(p, s);

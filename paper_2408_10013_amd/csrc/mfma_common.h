@@ -22,6 +22,7 @@ struct NtP {
   uint16_t *colsum;  // gemm_km256_k: if set, colsum[n] (+)= sum over k of the second operand (k, n), n = 0..N-1
   int colsum_acc;    //               nonzero: added to what colsum holds
   int stagger;  // gemm_km256_k: the workgroups of XCD x start their K loop x * stagger stages in (0 = all at stage 0)
+  int pf;       // gemm_km256_k: stages that the L2 prefetch runs ahead of the loads (0 = none)
 };
 
 __device__ __forceinline__ void unpack4(uint2 v, float *f) {
