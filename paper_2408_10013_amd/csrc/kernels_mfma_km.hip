@@ -446,13 +446,16 @@ static int stagger_for(int N, int K) {
 }
 
 // L2 prefetch distance by shape (0 = none).  It pays where the first operand is K-contiguous with rows far apart, i.e.
-// a long K (sustained, alone: 32768 x 8192 x 32768 K-contiguous +6 %, x 24576 +8 %, the forward product with K = 32768
-// +4 %), costs 2 % at K = 8192 (the touches take the address unit's time and there is less latency to hide), and is
-// a wash on the weight gradients, both of whose operands are k-major (-0.4 to +2 %).
+// a long K (sustained, alone: 32768 x 8192 x 24576 K-contiguous +7 %, the forward product with K = 32768 +4 %), costs
+// 2 % at K = 8192 (the touches take the address unit's time and there is less latency to hide), and is a wash on the
+// weight gradients, both of whose operands are k-major (-0.4 to +2 %).  Where both operands are K-contiguous with rows
+// a multiple of 32 KiB apart (32768 x 8192 x 32768) it is 5 % faster alone but doubles the bytes fetched (lines touched
+// early are evicted again before their stage: such rows share few L2 sets) and gives nothing in the layer: not used,
+// and that product stays with gemm_nt256_k.  One stage ahead is as good as two or three and fetches least.
 static int prefetch_for(int K, bool akm, bool bkm) {
-  (void)bkm;
   if (g_km_pf >= 0) return g_km_pf;
-  return (!akm && K >= 16384) ? 2 : 0;
+  if (!bkm && (K * 2) % 32768 == 0) return 0;
+  return (!akm && K >= 16384) ? 1 : 0;
 }
 
 bool gemm_km_fits(int M, int N, int K, bool transA, bool transB, int dtype) {
