@@ -123,8 +123,8 @@ hipError_t colreduce1_vec(const void *a, long lda, const void *x, const float *m
 hipError_t gemm_mfma_bf16(const Gemm &g, hipStream_t s);
 hipError_t gemm_mfma_km_bf16(const Gemm &g, hipStream_t s);  // reads k-major operands as stored; no scratch
 bool gemm_km_fits(int M, int N, int K, bool transA, bool transB, int dtype);  // shape conditions of that kernel
-extern int g_km_stagger;
-extern int g_km_pf;
+extern int g_km_stagger;  // stages between the K-loop starts of neighbouring XCDs (-100 = by shape)
+extern int g_km_pf;       // stages that the L2 prefetch runs ahead (-1 = by shape, 0 = none)
 extern int g_km_mode;  // 0 = off, 1 = for problems with a k-major operand (default), 2 = also for the NT form
 hipError_t attn_fwd_mfma_bf16(const Attn &a, hipStream_t s);
 hipError_t attn_bwd_mfma_bf16(const Attn &a, hipStream_t s);

@@ -26,6 +26,9 @@
 //   * LDS reads are compiler-visible (no inline assembly): the compiler computes every
 //     `s_waitcnt lgkmcnt` from the program order, which scheduling fences pin to the order written
 //     here.  The direct-to-LDS loads and the barrier are still written out, with `vmcnt` waits by hand.
+//   * Only wavefronts 4-7 load (a stage's 16 instructions in one burst behind the barrier), no two LDS
+//     reads are issued back to back, and instantiations for long K end the burst with an L2 prefetch
+//     (see the loader and the two halves of the stage below).
 #include "dev.h"
 #include "kernels.h"
 #include "mfma_common.h"
