@@ -741,6 +741,126 @@ __global__ void lse_base2_k(const float *lse, float *out, long n) {
   if (i < n) out[i] = lse[i] == -INFINITY ? INFINITY : lse[i] * kLog2e;
 }
 
+// ------------------------------------------------------------------------------------------
+// backward, query side, head size 128: the arithmetic of fa_bwd_dq_k with the tile traffic of fa_bwd_dkv128_k.
+// In fa_bwd_dq_k the K / V tile goes global -> registers -> LDS, eight 16-byte LDS stores per thread in one group
+// behind a barrier: the LDS data queue was full in 19 % of that kernel's cycles (SQ_LDS_DATA_FIFO_FULL), and a
+// wavefront that cannot hand over a store cannot issue what follows.  Here both tiles are unpadded, swizzled
+// (sw128) and double-buffered, filled by direct global-to-LDS loads issued one tile ahead: no LDS stores, no
+// staging registers, one barrier per tile.
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ void dq128_tile(const FaP &p, const uint16_t *sK, const uint16_t *sV, const bf16x8_t (&qf)[8],
+                                           const bf16x8_t (&dof)[8], f32x16_t (&dqacc)[4], float lse2, float delta, int j0,
+                                           int q0, int qi, int limit, int lane) {
+  constexpr int BKV = 64;
+  const int half = lane >> 5, li = lane & 31;
+  if (p.mask == SSDT_MASK_CAUSAL && j0 > q0 + 31) return;  // tile entirely above this wavefront's diagonal
+  const bool need_mask = (p.mask == SSDT_MASK_CAUSAL && j0 + BKV - 1 > q0) || (j0 + BKV > limit);
+  const float sc = p.scale * kLog2e;
+  // per-lane bases that the step / column-block index is XOR-ed into (as in dkv128_tile; the empty asm keeps the
+  // derived addresses from being hoisted out of the tile loop into long-lived registers)
+  const int sl = swz(li), L = lane & 15, kr = L >> 2, lowc = ((lane >> 4) & 1) * 2 + ((L & 3) >> 1);
+  int rbase = li * 128 + (((half ^ sl) & 1) << 3) + ((sl >> 1) << 4);
+  int t0 = (half * 4 + kr) * 128 + ((lowc ^ swz(half * 4 + kr)) << 3) + (L & 1) * 4;
+  int t1 = (half * 4 + 8 + kr) * 128 + ((lowc ^ swz(half * 4 + 8 + kr)) << 3) + (L & 1) * 4;
+  asm volatile("" : "+v"(rbase), "+v"(t0), "+v"(t1));
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb) {
+    f32x16_t sacc, dpacc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { sacc[r] = 0.f; dpacc[r] = 0.f; }
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      const bf16x8_t ka = *(const bf16x8_t *)(sK + kb * 32 * 128 + (rbase ^ (ks << 4)));
+      const bf16x8_t va = *(const bf16x8_t *)(sV + kb * 32 * 128 + (rbase ^ (ks << 4)));
+      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[ks], sacc, 0, 0, 0);
+      dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, dof[ks], dpacc, 0, 0, 0);
+    }
+    float dsv[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      float pe = __builtin_amdgcn_exp2f(fmaf(sacc[r], sc, -lse2));
+      if (need_mask) {
+        const int key = j0 + kb * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
+        if (key >= limit || (p.mask == SSDT_MASK_CAUSAL && key > qi)) pe = 0.f;
+      }
+      dsv[r] = pe * (dpacc[r] - delta);
+    }
+#pragma unroll
+    for (int gs = 0; gs < 2; ++gs) {
+      const bf16x8_t dsf = pack8(dsv + gs * 8, dsv + gs * 8 + 4);
+      const uint16_t *tb = sK + (kb * 32 + gs * 16) * 128;
+#pragma unroll
+      for (int d = 0; d < 4; ++d) {
+        union { struct { s16x4_t a, b; } s; bf16x8_t v; } u;
+        u.s.a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)(tb + (t0 ^ (d << 5))));
+        u.s.b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)(tb + (t1 ^ (d << 5))));
+        dqacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(u.v, dsf, dqacc[d], 0, 0, 0);
+      }
+    }
+  }
+}
+
+__global__ __launch_bounds__(256, 2) void fa_bwd_dq128_k(FaP p) {
+  constexpr int D = 128, BKV = 64;
+  __shared__ __attribute__((aligned(1024))) uint16_t sK0[BKV * D], sV0[BKV * D], sK1[BKV * D], sV1[BKV * D];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, half = lane >> 5, li = lane & 31;
+  const int nqb = p.Sq / 128;
+  int bx, h, b;
+  xcd_block(&bx, &h, &b);
+  const int qb = (p.mask == SSDT_MASK_CAUSAL) ? nqb - 1 - bx : bx;
+  const int q0 = qb * 128 + w * 32, qi = q0 + li;
+  const uint16_t *qp = p.q + (long)(b * p.Sq + qi) * p.ldq + h * D, *dop = p.dout + (long)(b * p.Sq + qi) * p.lddo + h * D;
+  bf16x8_t qf[8], dof[8];
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) {
+    qf[ks] = *(const bf16x8_t *)(qp + ks * 16 + half * 8);
+    dof[ks] = *(const bf16x8_t *)(dop + ks * 16 + half * 8);
+  }
+  const long si = ((long)b * p.A + h) * p.Sq + qi;
+  const float lse2 = p.lse[si], delta = p.delta[si];  // lse in base-2 units, +inf for a row without keys
+  int limit = p.Sk;
+  if (p.mask == SSDT_MASK_CAUSAL) limit = min(limit, qb * 128 + 128);
+  if (p.mask == SSDT_MASK_KEYPAD) limit = min(limit, max(0, p.kv_len[b]));
+  const int ntiles = (limit + BKV - 1) / BKV;  // whole tiles: Sk is a multiple of 128
+  f32x16_t dqacc[4];
+#pragma unroll
+  for (int d = 0; d < 4; ++d)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) dqacc[d][r] = 0.f;
+  const uint16_t *kg = p.k + (long)b * p.Sk * p.ldk + h * D, *vg = p.v + (long)b * p.Sk * p.ldv + h * D;
+  if (ntiles > 0) {
+    dma_tile128<BKV>(kg, (int)p.ldk, sK0, w, lane);
+    dma_tile128<BKV>(vg, (int)p.ldv, sV0, w, lane);
+  }
+  // tile t sits in buffer t & 1; while it is consumed the next tile loads into the other buffer
+  for (int t = 0; t < ntiles; t += 2) {
+    __builtin_amdgcn_s_waitcnt(0xF70);  // vmcnt(0): this wavefront's loads of the tile have landed
+    __syncthreads();                    // everyone's have, and everyone is done with the other buffer
+    if (t + 1 < ntiles) {
+      dma_tile128<BKV>(kg + (long)(t + 1) * BKV * p.ldk, (int)p.ldk, sK1, w, lane);
+      dma_tile128<BKV>(vg + (long)(t + 1) * BKV * p.ldv, (int)p.ldv, sV1, w, lane);
+    }
+    dq128_tile(p, sK0, sV0, qf, dof, dqacc, lse2, delta, t * BKV, q0, qi, limit, lane);
+    if (t + 1 >= ntiles) break;
+    __builtin_amdgcn_s_waitcnt(0xF70);
+    __syncthreads();
+    if (t + 2 < ntiles) {
+      dma_tile128<BKV>(kg + (long)(t + 2) * BKV * p.ldk, (int)p.ldk, sK0, w, lane);
+      dma_tile128<BKV>(vg + (long)(t + 2) * BKV * p.ldv, (int)p.ldv, sV0, w, lane);
+    }
+    dq128_tile(p, sK1, sV1, qf, dof, dqacc, lse2, delta, (t + 1) * BKV, q0, qi, limit, lane);
+  }
+  uint16_t *dqp = p.dq + (long)(b * p.Sq + qi) * p.lddq + h * D;
+#pragma unroll
+  for (int d = 0; d < 4; ++d)
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+      *(uint2 *)(dqp + d * 32 + g * 8 + half * 4) =
+          make_uint2(pack_bf2(dqacc[d][g * 4 + 0] * p.scale, dqacc[d][g * 4 + 1] * p.scale),
+                     pack_bf2(dqacc[d][g * 4 + 2] * p.scale, dqacc[d][g * 4 + 3] * p.scale));
+}
+
 int g_attn_kb = 0;  // test hook: 1 pins the register-staged key-side kernel
 
 hipError_t attn_bwd_mfma_bf16(const Attn &a, hipStream_t s) {
@@ -767,7 +887,10 @@ hipError_t attn_bwd_mfma_bf16(const Attn &a, hipStream_t s) {
                      g_attn_kb != 1;
     if (dma) hipLaunchKernelGGL(fa_bwd_dkv128_k, gk, dim3(256), 0, s, p);
     else hipLaunchKernelGGL(fa_bwd_dkv_k<128>, gk, dim3(256), 0, s, p);
-    hipLaunchKernelGGL(fa_bwd_dq_k<128>, gq, dim3(256), 0, s, p);
+    // (the query-side kernel's direct loads want K rows 16-byte aligned as well)
+    const bool dmaq = (((uintptr_t)a.k | (uintptr_t)a.v) & 15) == 0 && a.ldk % 8 == 0 && a.ldv % 8 == 0 && g_attn_kb != 1;
+    if (dmaq) hipLaunchKernelGGL(fa_bwd_dq128_k, gq, dim3(256), 0, s, p);
+    else hipLaunchKernelGGL(fa_bwd_dq_k<128>, gq, dim3(256), 0, s, p);
   } else {
     hipLaunchKernelGGL(fa_bwd_dkv_k<64>, gk, dim3(256), 0, s, p);
     hipLaunchKernelGGL(fa_bwd_dq_k<64>, gq, dim3(256), 0, s, p);
