@@ -298,13 +298,19 @@ static FaP to_fa(const Attn &a) {
   return p;
 }
 
+__global__ void fa_fwd128_k(FaP p);  // defined with the other direct-load kernels below
+extern int g_attn_kb;
+
 hipError_t attn_fwd_mfma_bf16(const Attn &a, hipStream_t s) {
   if (!fa_supported(a) || ((uintptr_t)a.o & 7) || a.ldo % 4) return hipErrorNotSupported;
   if (a.mask == SSDT_MASK_CAUSAL && a.Sq != a.Sk) return hipErrorNotSupported;
   FaP p = to_fa(a);
   prof::Scope ps(prof::ATTN_FWD, fa_flops(a), 0, s);
   dim3 grid(a.Sq / 128, a.A, a.B);
-  if (a.d == 128) hipLaunchKernelGGL(fa_fwd_k<128>, grid, dim3(256), 0, s, p);
+  // head size 128 with 16-byte aligned K / V rows: tiles by direct global-to-LDS loads
+  const bool dma = a.d == 128 && (((uintptr_t)a.k | (uintptr_t)a.v) & 15) == 0 && a.ldk % 8 == 0 && a.ldv % 8 == 0 && g_attn_kb != 1;
+  if (dma) hipLaunchKernelGGL(fa_fwd128_k, grid, dim3(256), 0, s, p);
+  else if (a.d == 128) hipLaunchKernelGGL(fa_fwd_k<128>, grid, dim3(256), 0, s, p);
   else hipLaunchKernelGGL(fa_fwd_k<64>, grid, dim3(256), 0, s, p);
   return hipGetLastError();
 }
@@ -742,6 +748,149 @@ __global__ void lse_base2_k(const float *lse, float *out, long n) {
 }
 
 // ------------------------------------------------------------------------------------------
+// forward, head size 128, with the tile traffic of fa_bwd_dkv128_k: K and V tiles unpadded, swizzled (sw128),
+// double-buffered and filled by direct global-to-LDS loads one tile ahead (fa_fwd_k stores them from registers, eight
+// 16-byte LDS stores per thread in one group: its LDS data queue was full in 29 % of its cycles).  Same arithmetic, in
+// the same order, as fa_fwd_k.
+// ------------------------------------------------------------------------------------------
+struct FwdState { float m, l; };
+
+__device__ __forceinline__ void fwd128_tile(const FaP &p, const uint16_t *sK, const uint16_t *sV, const bf16x8_t (&qf)[8],
+                                            f32x16_t (&oacc)[4], FwdState &st, int j0, int q0, int qi, int limit, int lane) {
+  constexpr int BKV = 64;
+  const int half = lane >> 5, li = lane & 31;
+  if (p.mask == SSDT_MASK_CAUSAL && j0 > q0 + 31) return;  // tile entirely above this wavefront's diagonal
+  const float sc = p.scale * kLog2e;
+  const int sl = swz(li), L = lane & 15, kr = L >> 2, lowc = ((lane >> 4) & 1) * 2 + ((L & 3) >> 1);
+  int rbase = li * 128 + (((half ^ sl) & 1) << 3) + ((sl >> 1) << 4);
+  int t0 = (half * 4 + kr) * 128 + ((lowc ^ swz(half * 4 + kr)) << 3) + (L & 1) * 4;
+  int t1 = (half * 4 + 8 + kr) * 128 + ((lowc ^ swz(half * 4 + 8 + kr)) << 3) + (L & 1) * 4;
+  asm volatile("" : "+v"(rbase), "+v"(t0), "+v"(t1));
+  f32x16_t sacc[2];
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) sacc[kb][r] = 0.f;
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      const bf16x8_t kf = *(const bf16x8_t *)(sK + kb * 32 * 128 + (rbase ^ (ks << 4)));
+      sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc[kb], 0, 0, 0);
+    }
+  const bool need_mask = (p.mask == SSDT_MASK_CAUSAL && j0 + BKV - 1 > q0) || (j0 + BKV > limit);
+  if (need_mask) {
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int key = j0 + kb * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
+        if (key >= limit || (p.mask == SSDT_MASK_CAUSAL && key > qi)) sacc[kb][r] = -INFINITY;
+      }
+  }
+  float mloc = -INFINITY;
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) mloc = fmaxf(mloc, sacc[kb][r]);
+  mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
+  // lazily moving reference point of the exponentials, as in fa_fwd_k
+  constexpr float kLazy = 8.f;
+  const float mnew = fmaxf(st.m, mloc);
+  const bool move = __builtin_amdgcn_ballot_w64((mnew - st.m) * sc > kLazy) != 0;
+  const float mref = move ? mnew : st.m, moff = (mref == -INFINITY) ? 0.f : -mref * sc;
+  if (move) {
+    const float corr = __builtin_amdgcn_exp2f(fmaf(st.m, sc, moff));
+    st.l *= corr;
+#pragma unroll
+    for (int d = 0; d < 4; ++d)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) oacc[d][r] *= corr;
+    st.m = mnew;
+  }
+  float lsum = 0.f;
+#pragma unroll
+  for (int s4 = 0; s4 < 4; ++s4) {
+    const int kb = s4 >> 1, g = (s4 & 1) * 2;
+    float pe[8];
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      pe[r] = __builtin_amdgcn_exp2f(fmaf(sacc[kb][g * 4 + r], sc, moff));
+      lsum += pe[r];
+    }
+    const bf16x8_t pf = pack8(pe, pe + 4);
+    const uint16_t *tb = sV + s4 * 16 * 128;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+      union { struct { s16x4_t a, b; } s; bf16x8_t v; } u;
+      u.s.a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)(tb + (t0 ^ (d << 5))));
+      u.s.b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)(tb + (t1 ^ (d << 5))));
+      oacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(u.v, pf, oacc[d], 0, 0, 0);
+    }
+  }
+  lsum += __shfl_xor(lsum, 32, 64);
+  st.l += lsum;
+}
+
+__global__ __launch_bounds__(256, 2) void fa_fwd128_k(FaP p) {
+  constexpr int D = 128, BKV = 64;
+  __shared__ __attribute__((aligned(1024))) uint16_t sK0[BKV * D], sV0[BKV * D], sK1[BKV * D], sV1[BKV * D];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, half = lane >> 5, li = lane & 31;
+  const int nqb = p.Sq / 128;
+  int bx, h, b;
+  xcd_block(&bx, &h, &b);
+  const int qb = (p.mask == SSDT_MASK_CAUSAL) ? nqb - 1 - bx : bx;  // long rows first
+  const int q0 = qb * 128 + w * 32, qi = q0 + li;
+  const uint16_t *qp = p.q + (long)(b * p.Sq + qi) * p.ldq + h * D;
+  bf16x8_t qf[8];
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) qf[ks] = *(const bf16x8_t *)(qp + ks * 16 + half * 8);
+  int limit = p.Sk;
+  if (p.mask == SSDT_MASK_CAUSAL) limit = min(limit, qb * 128 + 128);
+  if (p.mask == SSDT_MASK_KEYPAD) limit = min(limit, max(0, p.kv_len[b]));
+  const int ntiles = (limit + BKV - 1) / BKV;  // whole tiles: Sk is a multiple of 128
+  FwdState st{-INFINITY, 0.f};
+  f32x16_t oacc[4];
+#pragma unroll
+  for (int d = 0; d < 4; ++d)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) oacc[d][r] = 0.f;
+  const uint16_t *kg = p.k + (long)b * p.Sk * p.ldk + h * D, *vg = p.v + (long)b * p.Sk * p.ldv + h * D;
+  if (ntiles > 0) {
+    dma_tile128<BKV>(kg, (int)p.ldk, sK0, w, lane);
+    dma_tile128<BKV>(vg, (int)p.ldv, sV0, w, lane);
+  }
+  for (int t = 0; t < ntiles; t += 2) {
+    __builtin_amdgcn_s_waitcnt(0xF70);  // vmcnt(0): this wavefront's loads of the tile have landed
+    __syncthreads();                    // everyone's have, and everyone is done with the other buffer
+    if (t + 1 < ntiles) {
+      dma_tile128<BKV>(kg + (long)(t + 1) * BKV * p.ldk, (int)p.ldk, sK1, w, lane);
+      dma_tile128<BKV>(vg + (long)(t + 1) * BKV * p.ldv, (int)p.ldv, sV1, w, lane);
+    }
+    fwd128_tile(p, sK0, sV0, qf, oacc, st, t * BKV, q0, qi, limit, lane);
+    if (t + 1 >= ntiles) break;
+    __builtin_amdgcn_s_waitcnt(0xF70);
+    __syncthreads();
+    if (t + 2 < ntiles) {
+      dma_tile128<BKV>(kg + (long)(t + 2) * BKV * p.ldk, (int)p.ldk, sK0, w, lane);
+      dma_tile128<BKV>(vg + (long)(t + 2) * BKV * p.ldv, (int)p.ldv, sV0, w, lane);
+    }
+    fwd128_tile(p, sK1, sV1, qf, oacc, st, (t + 1) * BKV, q0, qi, limit, lane);
+  }
+  const float inv = st.l > 0.f ? 1.f / st.l : 0.f;
+  uint16_t *op = p.out + (long)(b * p.Sq + qi) * p.ldo + h * D;
+#pragma unroll
+  for (int d = 0; d < 4; ++d)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      uint2 v = make_uint2(pack_bf2(oacc[d][g * 4 + 0] * inv, oacc[d][g * 4 + 1] * inv),
+                           pack_bf2(oacc[d][g * 4 + 2] * inv, oacc[d][g * 4 + 3] * inv));
+      *(uint2 *)(op + d * 32 + g * 8 + half * 4) = v;
+    }
+  if (half == 0) p.lse[((long)b * p.A + h) * p.Sq + qi] = st.l > 0.f ? st.m * p.scale + logf(st.l) : -INFINITY;
+}
+
+// ------------------------------------------------------------------------------------------
 // backward, query side, head size 128: the arithmetic of fa_bwd_dq_k with the tile traffic of fa_bwd_dkv128_k.
 // In fa_bwd_dq_k the K / V tile goes global -> registers -> LDS, eight 16-byte LDS stores per thread in one group
 // behind a barrier: the LDS data queue was full in 19 % of that kernel's cycles (SQ_LDS_DATA_FIFO_FULL), and a
@@ -861,7 +1010,7 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dq128_k(FaP p) {
                      pack_bf2(dqacc[d][g * 4 + 2] * p.scale, dqacc[d][g * 4 + 3] * p.scale));
 }
 
-int g_attn_kb = 0;  // test hook: 1 pins the register-staged key-side kernel
+int g_attn_kb = 0;  // test hook: 1 pins the register-staged kernels
 
 hipError_t attn_bwd_mfma_bf16(const Attn &a, hipStream_t s) {
   if (!fa_supported(a)) return hipErrorNotSupported;
