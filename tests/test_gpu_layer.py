@@ -139,6 +139,9 @@ VARIANTS = {
     # shapes the matrix-core kernels take (multiples of 128; head size 64 / 128)
     "gpt_mfma": dict(arch="gpt_preln", B=2, S=256, H=256, A=2, F=1024, act="gelu", norm="layernorm", mask="causal", has_bias=True, eps=1e-5),
     "bert_mfma": dict(arch="bert_postln", B=3, S=128, H=256, A=4, F=512, act="gelu", norm="layernorm", mask="keypad", has_bias=True, eps=1e-5),
+    # head size 128 with key padding: the direct-load attention kernels with ragged valid lengths (a last tile that is
+    # partly masked, sequences shorter than one tile)
+    "bert_d128": dict(arch="bert_postln", B=3, S=256, H=256, A=2, F=512, act="gelu", norm="layernorm", mask="keypad", has_bias=True, eps=1e-5),
     "t5enc_mfma": dict(arch="t5_enc", B=2, S=128, H=128, A=2, F=384, act="relu", norm="rmsnorm", mask="none", has_bias=False, eps=1e-6),
     "t5dec_mfma": dict(arch="t5_dec", B=2, S=128, S_kv=256, H=128, A=2, F=256, act="relu", norm="rmsnorm", mask="causal", has_bias=False, eps=1e-6),
     # 4096 x 4096 outputs (256 tiles of 256 x 256: the large-tile GEMM kernel) over a contraction of only two
@@ -176,7 +179,7 @@ def test_layer_variants_small(name, dtype):
         assert torch.equal(on["d_enc"], off["d_enc"])
 
 
-@pytest.mark.parametrize("name", ["bert_keypad", "bert_mfma"])
+@pytest.mark.parametrize("name", ["bert_keypad", "bert_mfma", "bert_d128"])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_sequence_without_any_admissible_key(name, dtype):
     """Degenerate case of the key-padding mask: one sequence of valid length 0.  Every one of its query rows has
